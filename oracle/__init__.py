@@ -1,0 +1,29 @@
+"""CPU oracle for the MuLo-SD parallel verification step.
+
+TEST INFRASTRUCTURE ONLY.  This package is a plain, slow, obviously-correct
+CPU statement of what the verification step computes (numpy / torch-CPU,
+float64 unless a rounding point is stated).  It shares no code with the HIP
+library and never imports it.  Only the test-suite, the smoke check and the
+benchmark's cpu-baseline leg may import it; the product path never does.
+
+Modules (each function cites the passage of the paper it follows):
+  philox    counter-based uniforms (the paper names no generator; Philox4x32-10,
+            Salmon et al. SC'11, is this build's choice)
+  upsample  Step 2: draft tokens / distributions onto the target grid (Sec. 3.2)
+  decoder   Step 3: target forward over the draft block against a KV cache
+  accept    Step 4: softmax, pooled mass (Eq. 3), accept test (Eq. 1)
+  local     Step 5: local neighbourhood expansion (Eq. 6-7)
+  resample  residual resampling (Eq. 2) through an integer CDF
+  step      the whole verification step (Alg. 1 Steps 2-5 + one-shot resample)
+
+Pin status (see tests/test_oracle_*.py):
+  upsample, accept, local, resample, step : pinned (invariants, closed forms,
+      brute force, exact enumeration).
+  decoder : structure pinned (causality, textbook special cases, float64
+      triple-loop pieces); the logit VALUES for random weights have no external
+      reference -> "parity unpinned" for the values themselves.
+  philox  : uniformity / independence pinned statistically; its identity as
+      Philox4x32-10 has no known-answer vector available here -> the constants
+      are "parity unpinned" (any good counter-based generator satisfies the
+      method, which fixes none).
+"""

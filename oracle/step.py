@@ -1,0 +1,70 @@
+"""The whole verification step (Alg. 1 Steps 2-5, plus the one-shot residual
+resampling of the marked positions that stands in for Step 6).  Test
+infrastructure; composes the other oracle modules in the order of the paper.
+"""
+import numpy as np
+
+from . import accept as A
+from . import local as LOC
+from . import philox as PH
+from . import resample as RS
+from . import upsample as UP
+
+
+def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1,
+           seed=0, rng_counter=0, nbr=None, mode=0):
+    """Decision stage on given logits (Sec. 3.1 Eq. 1-3, Sec. 3.3 Eq. 6-7).
+
+    logits: float [B, L, V]; q_rows: float32 [B, n_q, V]; q_row_index: int [L]
+    or None (identity); draft_tokens: int [B, L].
+    Returns a dict of arrays: p, pbar, q_tok, u, accept, near_tie, mask, t0,
+    tokens_out, stats [B, 4] = (accepted, rejected, marked, near ties).
+    """
+    logits = np.asarray(logits)
+    B, L, V = logits.shape
+    qi = np.arange(L) if q_row_index is None else np.asarray(q_row_index).astype(np.int64)
+    toks = np.asarray(draft_tokens).astype(np.int64).reshape(B, L)
+    u = PH.uniform24(PH.step_words(seed, rng_counter, PH.STREAM_ACCEPT, B, L))
+    words = PH.step_words(seed, rng_counter, PH.STREAM_SAMPLE, B, L)
+    out = dict(p=np.empty((B, L, V), np.float32), pbar=np.empty((B, L), np.float32),
+               q_tok=np.empty((B, L), np.float32), u=u, words=words,
+               accept=np.empty((B, L), np.uint8), near_tie=np.empty((B, L), bool),
+               mask=np.empty((B, L), np.uint8), t0=np.empty(B, np.int32),
+               tokens_out=np.empty((B, L), np.int32), stats=np.zeros((B, 4), np.int32))
+    for b in range(B):
+        p = A.target_probs(logits[b])                                   # Step 3 -> p_i
+        pbar = A.pooled_mass(p, toks[b], nbr)                           # Eq. 3 numerator
+        q_tok = np.asarray(q_rows[b], dtype=np.float32)[qi, toks[b]]    # q_i(x~_i)
+        acc = A.accept_test(pbar, q_tok, u[b])                          # Eq. 1
+        mask, t0 = LOC.local_mask(acc, W, n0, radius, expand)           # Eq. 6-7
+        tok_out = RS.resample_block(p, np.asarray(q_rows[b], dtype=np.float32), qi,
+                                    toks[b], mask, acc, words[b], mode)  # Eq. 2
+        nt = A.near_tie(pbar, q_tok, u[b])
+        out["p"][b], out["pbar"][b], out["q_tok"][b] = p, pbar, q_tok
+        out["accept"][b], out["near_tie"][b] = acc, nt
+        out["mask"][b], out["t0"][b], out["tokens_out"][b] = mask, t0, tok_out
+        out["stats"][b] = (int(acc.sum()), int(L - acc.sum()), int(mask.sum()), int(nt.sum()))
+    return out
+
+
+def verify_step(decoder, P, draft_lo, draft_tokens_lo, prev_tokens, *, h_blk, w, r, W, n0,
+                radius, expand=1, seed=0, rng_counter=0, nbr=None, mode=0,
+                input_is_probs=False):
+    """Steps 2-5 + resampling for one block of L = (r*h_blk)*(r*w) positions.
+
+    decoder: oracle.decoder.DecoderOracle whose cache holds P valid rows;
+    draft_lo: [B, h_blk*w, V] draft logits (or probabilities) of the low-res rows
+    behind this block; draft_tokens_lo: [B, h_blk*w]; prev_tokens: [B] the last
+    committed (or last prefix) token.  Target inputs are [prev, x~_0 .. x~_{L-2}],
+    so logit row j is p for draft position j (Alg. 1 Step 3).
+    """
+    tokens_hi, q_lo, q_row, _ = UP.upsample_draft(draft_lo, draft_tokens_lo, h_blk, w, r,
+                                                  input_is_probs=input_is_probs)
+    B, L = tokens_hi.shape
+    inp = np.concatenate([np.asarray(prev_tokens).reshape(B, 1).astype(np.int32),
+                          tokens_hi[:, :L - 1]], axis=1)
+    logits = decoder.forward(inp, P).numpy()
+    out = decide(logits, q_lo, q_row, tokens_hi, W=W, n0=n0, radius=radius, expand=expand,
+                 seed=seed, rng_counter=rng_counter, nbr=nbr, mode=mode)
+    out.update(tokens_hi=tokens_hi, q_lo=q_lo, q_row=q_row, logits=logits)
+    return out

@@ -1,0 +1,237 @@
+"""Pins for the oracle's target forward: structure (causality, cache writes,
+batch independence), textbook special cases, and a scalar brute force on a toy
+model.  The logit VALUES for random weights have no outside reference
+("parity unpinned" beyond these checks).  CPU only."""
+import math
+
+import numpy as np
+import torch
+
+from oracle import decoder as D
+from workloads import generators as G
+
+
+def _toy(nl=2, d=8, nh=2, dh=4, f=12, V=16, dtype="f32", seed=0, std=0.3):
+    m = dict(n_layers=nl, d_model=d, n_heads=nh, head_dim=dh, d_ffn=f, vocab=V, dtype=dtype,
+             rms_eps=1e-5)
+    w = G.make_weights(m, seed=seed, std=std, threads=1)
+    # non-trivial norm gains so that a dropped gain would show
+    g = torch.Generator().manual_seed(seed)
+    for k in ("attn_norm", "ffn_norm", "final_norm"):
+        w[k] = (1 + 0.2 * torch.randn(w[k].shape, generator=g)).to(w[k].dtype)
+    return m, w
+
+
+def _oracle(m, w, B, S, rb=False):
+    cos, sin = G.rope_table(S, m["head_dim"])
+    return D.DecoderOracle(m, w, cos, sin, B, S, round_bf16=rb)
+
+
+# ---------------------------------------------------------------- brute force
+def _scalar_forward(m, w, cos, sin, tokens_all):
+    """Whole-sequence decoder, one sequence, python floats and explicit loops;
+    attention for position t runs over positions 0..t.  Returns logits [T][V]."""
+    nl, d, nh, dh, f, V = (m[k] for k in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab"))
+    W = {k: v.double().tolist() for k, v in w.items()}
+    T = len(tokens_all)
+    x = [[W["embed"][tok][c] for c in range(d)] for tok in tokens_all]
+
+    def norm(row, g):
+        ms = sum(v * v for v in row) / len(row)
+        return [v / math.sqrt(ms + m["rms_eps"]) * g[c] for c, v in enumerate(row)]
+
+    def matvec(M, row):          # M [out][in]
+        return [sum(M[o][i] * row[i] for i in range(len(row))) for o in range(len(M))]
+
+    def rot(vec, pos):
+        out = list(vec)
+        for hh in range(nh):
+            for mm in range(dh // 2):
+                a, b = vec[hh * dh + 2 * mm], vec[hh * dh + 2 * mm + 1]
+                c, s = float(cos[pos][mm]), float(sin[pos][mm])
+                out[hh * dh + 2 * mm] = a * c - b * s
+                out[hh * dh + 2 * mm + 1] = a * s + b * c
+        return out
+
+    for l in range(nl):
+        xh = [norm(x[t], W["attn_norm"][l]) for t in range(T)]
+        q = [rot(matvec(W["wq"][l], xh[t]), t) for t in range(T)]
+        k = [rot(matvec(W["wk"][l], xh[t]), t) for t in range(T)]
+        v = [matvec(W["wv"][l], xh[t]) for t in range(T)]
+        for t in range(T):
+            att = [0.0] * d
+            for hh in range(nh):
+                sl = slice(hh * dh, (hh + 1) * dh)
+                sc = [sum(a * b for a, b in zip(q[t][sl], k[s][sl])) / math.sqrt(dh) for s in range(t + 1)]
+                mx = max(sc)
+                e = [math.exp(v_ - mx) for v_ in sc]
+                z = sum(e)
+                for c in range(dh):
+                    att[hh * dh + c] = sum(e[s] / z * v[s][hh * dh + c] for s in range(t + 1))
+            o = matvec(W["wo"][l], att)
+            x[t] = [a + b for a, b in zip(x[t], o)]
+        for t in range(T):
+            xh_t = norm(x[t], W["ffn_norm"][l])
+            gte = matvec(W["w_gate"][l], xh_t)
+            up = matvec(W["w_up"][l], xh_t)
+            hmid = [(g_ / (1 + math.exp(-g_))) * u_ for g_, u_ in zip(gte, up)]
+            o = matvec(W["w_down"][l], hmid)
+            x[t] = [a + b for a, b in zip(x[t], o)]
+    return [matvec(W["lm_head"], norm(x[t], W["final_norm"])) for t in range(T)]
+
+
+def test_forward_matches_scalar_brute_force_with_prefix_and_block():
+    m, w = _toy()
+    S = 7
+    cos, sin = G.rope_table(S, m["head_dim"])
+    toks = G.uniform_tokens((2, S), m["vocab"], seed=3)
+    orc = _oracle(m, w, 2, S)
+    P = 3
+    orc.forward(toks[:, :P], 0)                       # prefill
+    z = orc.forward(toks[:, P:], P).numpy()           # block against the cache
+    for b in range(2):
+        want = np.array(_scalar_forward(m, w, cos, sin, toks[b].tolist()))
+        assert np.abs(z[b] - want[P:]).max() < 1e-10
+
+
+def test_block_pass_equals_token_by_token():
+    m, w = _toy(nl=3, d=16, nh=4, dh=4, f=20, V=32, seed=1)
+    B, P, L = 2, 5, 12
+    toks = G.uniform_tokens((B, P + L), m["vocab"], seed=4)
+    a = _oracle(m, w, B, P + L)
+    a.forward(toks[:, :P], 0)
+    z_block = a.forward(toks[:, P:], P).numpy()
+    b = _oracle(m, w, B, P + L)
+    b.forward(toks[:, :P], 0)
+    z_seq = np.concatenate([b.forward(toks[:, P + j:P + j + 1], P + j).numpy() for j in range(L)], axis=1)
+    assert np.abs(z_block - z_seq).max() < 1e-10
+    assert torch.allclose(a.k, b.k, atol=1e-12) and torch.allclose(a.v, b.v, atol=1e-12)
+    # logits of position j do not depend on later inputs
+    toks2 = toks.copy()
+    toks2[:, P + 7:] = (toks2[:, P + 7:] + 1) % m["vocab"]
+    c = _oracle(m, w, B, P + L)
+    c.forward(toks2[:, :P], 0)
+    z2 = c.forward(toks2[:, P:], P).numpy()
+    assert np.abs(z2[:, :7] - z_block[:, :7]).max() == 0
+    assert np.abs(z2[:, 7:] - z_block[:, 7:]).max() > 1e-6
+
+
+def test_cache_rows_and_batch_permutation():
+    m, w = _toy(seed=2)
+    B, P, L, S = 3, 4, 6, 12
+    toks = G.uniform_tokens((B, P + L), m["vocab"], seed=5)
+    o = _oracle(m, w, B, S)
+    o.forward(toks[:, :P], 0)
+    k_before = o.k.clone()
+    z = o.forward(toks[:, P:], P).numpy()
+    assert torch.equal(o.k[:, :, :P], k_before[:, :, :P])             # rows < P untouched
+    assert o.k[:, :, P + L:].abs().max() == 0                          # rows >= P+L untouched
+    assert o.k[:, :, P:P + L].abs().min() > 0
+    perm = [2, 0, 1]
+    o2 = _oracle(m, w, B, S)
+    o2.forward(toks[perm, :P], 0)
+    z2 = o2.forward(toks[perm, P:], P).numpy()
+    assert np.abs(z2 - z[perm]).max() < 1e-12
+
+
+def test_single_token_attention_returns_its_value_row():
+    # L = 1, P = 0: softmax over one key is 1, so the attention output is v_0 and the
+    # layer reduces to x + v Wo^T followed by the feed-forward, whatever wq and wk hold.
+    m, w = _toy(nl=1, seed=6)
+    tok = np.array([[5]])
+    z = _oracle(m, w, 1, 4).forward(tok, 0).numpy()
+    w2 = dict(w)
+    w2["wq"] = torch.randn_like(w["wq"])
+    w2["wk"] = torch.randn_like(w["wk"])
+    z2 = _oracle(m, w2, 1, 4).forward(tok, 0).numpy()
+    assert np.abs(z - z2).max() < 1e-12
+
+
+def test_embeds_input_equals_token_input():
+    m, w = _toy(seed=7)
+    toks = G.uniform_tokens((2, 5), m["vocab"], seed=8)
+    z = _oracle(m, w, 2, 5).forward(toks, 0).numpy()
+    emb = w["embed"].double()[torch.as_tensor(toks).long()].numpy()
+    z2 = _oracle(m, w, 2, 5).forward(toks * 0, 0, embeds=emb).numpy()
+    assert np.abs(z - z2).max() < 1e-12
+
+
+# ------------------------------------------------------------- the pieces
+def test_round_to_bf16_matches_library_cast_and_ties():
+    g = torch.Generator().manual_seed(0)
+    x32 = torch.randn(200000, generator=g) * torch.exp(4 * torch.randn(200000, generator=g))
+    got = D.round_to_bf16(x32.double())
+    want = x32.to(torch.bfloat16).double()             # library cast (single rounding from float32)
+    assert torch.equal(got, want)
+    # exact ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    t = torch.tensor([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8), 1 + 2.0 ** -8 + 2.0 ** -40],
+                     dtype=torch.float64)
+    assert D.round_to_bf16(t).tolist() == [1.0, 1 + 2.0 ** -6, -1.0, 1 + 2.0 ** -7]
+    # bf16 values are fixed points
+    assert torch.equal(D.round_to_bf16(want), want)
+
+
+def test_rmsnorm_rotary_silu_properties():
+    g = torch.Generator().manual_seed(1)
+    x = torch.randn(5, 64, generator=g, dtype=torch.float64) * 3
+    y = D.rmsnorm(x, torch.ones(64, dtype=torch.float64), 0.0)
+    assert torch.allclose((y * y).mean(-1), torch.ones(5, dtype=torch.float64), atol=1e-12)
+    assert torch.allclose(D.rmsnorm(7 * x, torch.ones(64, dtype=torch.float64), 0.0), y, atol=1e-12)
+    gain = torch.randn(64, generator=g, dtype=torch.float64)
+    assert torch.allclose(D.rmsnorm(x, gain, 1e-5), D.rmsnorm(x, torch.ones(64, dtype=torch.float64), 1e-5) * gain)
+    # eps: a zero row stays zero (no division by zero)
+    assert D.rmsnorm(torch.zeros(1, 8, dtype=torch.float64), torch.ones(8, dtype=torch.float64), 1e-5).abs().max() == 0
+    # rotary: position 0 is the identity, norms are preserved, and q.k depends on the position difference only
+    cos, sin = G.rope_table(40, 8)
+    cos, sin = torch.tensor(cos).double(), torch.tensor(sin).double()
+    t = torch.randn(1, 1, 2, 8, generator=g, dtype=torch.float64)
+    assert torch.allclose(D.rotary(t, cos[0:1], sin[0:1]), t)
+    r5 = D.rotary(t, cos[5:6], sin[5:6])
+    assert torch.allclose(r5.norm(dim=-1), t.norm(dim=-1))
+    s = torch.randn(1, 1, 2, 8, generator=g, dtype=torch.float64)
+    dot = lambda a, b: (D.rotary(t, cos[a:a + 1], sin[a:a + 1]) * D.rotary(s, cos[b:b + 1], sin[b:b + 1])).sum()
+    assert abs(dot(3, 10) - dot(20, 27)) < 1e-5       # table is float32: agreement to its rounding
+    # first pair rotates by the angle `pos` (theta_0 = 1): 2-D rotation closed form
+    e0 = torch.zeros(1, 1, 1, 8, dtype=torch.float64)
+    e0[..., 0] = 1
+    r = D.rotary(e0, cos[2:3], sin[2:3])[0, 0, 0]
+    assert abs(r[0] - math.cos(2)) < 1e-7 and abs(r[1] - math.sin(2)) < 1e-7
+    # silu
+    v = torch.linspace(-6, 6, 25, dtype=torch.float64)
+    assert torch.allclose(D.silu(v) - D.silu(-v), v, atol=1e-12)
+    assert D.silu(torch.zeros(1, dtype=torch.float64)) == 0
+    assert torch.allclose(D.silu(v), torch.nn.functional.silu(v), atol=1e-12)
+
+
+def test_bf16_contract_keeps_logits_close_to_unrounded():
+    # rounding at the stated points perturbs logits at the bf16 level only
+    m, w = _toy(nl=2, d=32, nh=4, dh=8, f=48, V=64, dtype="bf16", seed=9, std=0.2)
+    toks = G.uniform_tokens((1, 10), m["vocab"], seed=10)
+    z_r = _oracle(m, w, 1, 10, rb=True).forward(toks, 0).numpy()
+    z_u = _oracle(m, w, 1, 10, rb=False).forward(toks, 0).numpy()
+    err = np.abs(z_r - z_u).max()
+    assert 0 < err < 0.05 * np.abs(z_u).max()
+    o = _oracle(m, w, 1, 10, rb=True)
+    o.forward(toks, 0)
+    assert torch.equal(o.k, o.k.to(torch.bfloat16).to(o.k.dtype))      # cache holds bf16 values
+
+
+# ------------------------------------------------------------- generators
+def test_generators_are_seeded_and_shaped():
+    m = dict(n_layers=2, d_model=64, n_heads=4, head_dim=16, d_ffn=96, vocab=128, dtype="bf16")
+    w1, w2 = G.make_weights(m, seed=1), G.make_weights(m, seed=1)
+    w3 = G.make_weights(m, seed=2)
+    assert all(torch.equal(w1[k], w2[k]) for k in w1)
+    assert not torch.equal(w1["wq"], w3["wq"]) and not torch.equal(w1["wq"][0], w1["wq"][1])
+    assert w1["w_gate"].shape == (2, 96, 64) and w1["w_down"].shape == (2, 64, 96)
+    assert w1["wq"].dtype == torch.bfloat16
+    assert abs(w1["lm_head"].float().std().item() - 0.02) < 2e-3
+    cos, sin = G.rope_table(16, 16)
+    assert cos.shape == (16, 8) and np.allclose(cos ** 2 + sin ** 2, 1, atol=1e-6)
+    t = G.uniform_tokens((3, 50), 128, seed=0)
+    assert t.min() >= 0 and t.max() < 128 and t.dtype == np.int32
+    nb = G.neighbour_table(32, 5, seed=0)
+    assert (nb[:, 0] == np.arange(32)).all() and all(len(set(r)) == 5 for r in nb.tolist())
+    lg = np.log(np.array([[0.7, 0.2, 0.1]] * 20000))
+    s = G.sample_categorical(lg, seed=0)
+    assert np.abs(np.bincount(s, minlength=3) / 20000 - [0.7, 0.2, 0.1]).max() < 0.02
