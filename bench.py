@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the MuLo-SD verification step (libmulo) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--no-cpu-baseline]
+
+One "step" = one mulo_verify_step call (up-sample -> target forward over the
+draft block against the KV cache -> accept test -> local expansion -> residual
+re-draw) over one batch of synthetic input already resident in HBM.  Prints ONE
+JSON line: verified image tokens/s (B*L / step time), a roofline object for the
+dominant kernel (the gate|up projection GEMM, bf16 MFMA bound) measured with HIP
+events on the library's stream during the timed steps, per-kernel-class figures,
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(c, w, cos, sin, seed):
+    """The oracle as it stands on a bounded sample: batch element 0, one grid row
+    (W tokens) as the draft block, against the full-length seeded cache."""
+    import numpy as np
+    import torch
+
+    from oracle import decoder as OD
+    from oracle import step as OS
+    from workloads import generators as G
+    m = c["model"]
+    nl, nh, dh, V = m["n_layers"], m["n_heads"], m["head_dim"], m["vocab"]
+    Ls = c["W"] * c["r"]                  # r grid rows: the smallest whole-row block the up-sampler can feed
+    P = c["max_seq"] - c["L"]
+    dec = OD.DecoderOracle(m, w, cos, sin, 1, P + Ls, round_bf16=(m["dtype"] == "bf16"))
+    dec.k[:, 0, :P] = G.random_kv((nl, nh, P, dh), seed, tag=0).permute(0, 2, 1, 3).to(dec.k.dtype)
+    dec.v[:, 0, :P] = G.random_kv((nl, nh, P, dh), seed, tag=1).permute(0, 2, 1, 3).to(dec.v.dtype)
+    n_lo = Ls // (c["r"] * c["r"])
+    dl = G.normal_logits((1, n_lo, V), 2.0, seed, tag=7)
+    dt = G.sample_categorical(dl, seed, tag=7)
+    threads = torch.get_num_threads()
+    t0 = time.perf_counter()
+    OS.verify_step(dec, P, dl, dt, np.zeros(1, np.int32), h_blk=1, w=c["w"], r=c["r"], W=c["W"],
+                   n0=c["T"] - c["L"], radius=c["radius"], expand=c["expand"], seed=seed, rng_counter=0)
+    dt_s = time.perf_counter() - t0
+    return {"value": Ls / dt_s, "unit": "verified tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "batch element 0, one %d-token block (%d grid rows) at P=%d of workload %s, all %d layers, "
+                      "float64; %.1f s including the per-call bf16->float64 weight conversion" % (
+                          Ls, c["r"], P, c["name"], nl, dt_s)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--sigma", type=float, default=None, help="draft-logit noise std (default: the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2601_05149_amd as mulo
+    from workloads import configs as WC
+    from workloads import generators as G
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    mulo.load_library()                   # fails loudly if the HIP library is not built
+    dev = "cuda:0"
+    c = WC.get(a.workload)
+    m = c["model"]
+    B, L, V, seed = c["B"], c["L"], m["vocab"], c["seed"]
+    sigma = a.sigma if a.sigma is not None else (c["sigma"] if c["sigma"] is not None else 1.0)
+    P = c["max_seq"] - L                  # last block of the image: the largest cache
+    n0 = c["T"] - L
+    h_blk = L // c["W"] // c["r"]
+    n_lo = h_blk * c["w"]
+
+    log("workload %s: B=%d L=%d P=%d V=%d; generating weights ..." % (c["name"], B, L, P, V))
+    w = G.make_weights(m, seed=seed)
+    cos, sin = G.rope_table(c["max_seq"], m["head_dim"])
+    wd = {k: v.to(dev) for k, v in w.items()}
+    cfg = mulo.make_cfg(m, B, c["max_seq"], L)
+    ctx = mulo.mulo_create(cfg, wd, torch.tensor(cos, device=dev), torch.tensor(sin, device=dev))
+    kv = mulo.alloc_kv(ctx, dev)
+    # cache rows [0, P): seeded N(0, 1) values (a stand-in for the prefilled prefix + committed blocks)
+    gen = torch.Generator(device=dev).manual_seed(seed)
+    kv[0][:, :, :, :P].normal_(generator=gen)
+    kv[1][:, :, :, :, :P].normal_(generator=gen)
+
+    # draft recipe ("target-like logits + N(0, sigma)"): provisional uniform draft -> un-timed forward ->
+    # draft logits = target logits of the top-left child + sigma * noise -> draft tokens ~ softmax(draft logits)
+    prov = torch.randint(0, V, (B, n_lo), generator=gen, device=dev, dtype=torch.int32)
+    thi = torch.empty(B, L, dtype=torch.int32, device=dev)
+    q_lo = torch.empty(B, n_lo, V, device=dev)
+    q_row = torch.empty(L, dtype=torch.int32, device=dev)
+    mulo.mulo_upsample_draft(ctx, B, h_blk, c["w"], c["r"], torch.zeros(B, n_lo, V, device=dev), 0, prov, thi, q_lo,
+                             q_row, None)
+    prev = torch.randint(0, V, (B,), generator=gen, device=dev, dtype=torch.int32)
+    inp = torch.cat([prev.reshape(B, 1), thi[:, :L - 1]], dim=1).contiguous()
+    zp = torch.empty(B, L, V, device=dev)
+    mulo.mulo_verify_forward(ctx, kv, B, L, P, inp, None, zp)
+    r = c["r"]
+    child0 = (torch.arange(h_blk, device=dev)[:, None] * r * c["W"] + torch.arange(c["w"], device=dev)[None, :] * r).reshape(-1)
+    draft_logits = (zp[:, child0, :] + sigma * torch.randn(B, n_lo, V, generator=gen, device=dev)).contiguous()
+    gumbel = -torch.log(-torch.log(torch.rand(B, n_lo, V, generator=gen, device=dev).clamp_min(1e-20)))
+    draft_tokens = (draft_logits + gumbel).argmax(-1).to(torch.int32).contiguous()
+    del zp, gumbel, q_lo
+
+    out = dict(tokens_out=torch.empty(B, L, dtype=torch.int32, device=dev),
+               accept=torch.empty(B, L, dtype=torch.uint8, device=dev),
+               mask=torch.empty(B, L, dtype=torch.uint8, device=dev),
+               t0=torch.empty(B, dtype=torch.int32, device=dev),
+               stats=torch.empty(B, 4, dtype=torch.int32, device=dev))
+
+    def step(i):
+        params = mulo.make_params(c["H"], c["W"], n0, L, c["radius"], c["expand"], seed=seed, rng_counter=i)
+        mulo.mulo_verify_step(ctx, kv, B, P, params, h_blk, c["w"], r, draft_logits, 0, draft_tokens, prev,
+                              out["tokens_out"], out["accept"], out["mask"], out["t0"], out["stats"])
+
+    log("warm-up ...")
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    if not a.no_profile:
+        mulo.mulo_profile(ctx, 1)
+    t_start = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t_start
+    prof = mulo.mulo_profile_read(ctx) if not a.no_profile else {}
+    mulo.mulo_profile(ctx, 0)
+    ms_per_step = 1e3 * dt_s / a.steps
+    stats = out["stats"].cpu().numpy()
+    acc_rate = float(stats[:, 0].sum()) / (B * L)
+    marked = float(stats[:, 2].sum()) / (B * L)
+
+    # algorithmic work per launch
+    d, f, nl = m["d_model"], m["d_ffn"], m["n_layers"]
+    M = B * L
+    flops = {"gemm_qkv": 2.0 * M * 3 * d * d, "gemm_out": 2.0 * M * d * d, "gemm_gate_up": 2.0 * M * 2 * f * d,
+             "gemm_down": 2.0 * M * d * f, "gemm_lm_head": 2.0 * M * V * d,
+             # causal attention: query j sees P + j + 1 keys; 4 * d flops per (query, key)
+             "attention": 4.0 * d * B * sum(P + j + 1 for j in range(L))}
+    byts = {"upsample": 2.0 * 4 * V * B * n_lo,            # read draft logits, write q_lo
+            "accept": 4.0 * V * M,                        # logits once
+            "mask_sample": 8.0 * V * M * marked}          # logits + draft row of every marked position
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        if n == 0:
+            continue
+        avg = ms / n
+        e = {"avg_ms": round(avg, 4), "launches_per_step": n / a.steps}
+        if name in flops:
+            e.update(bound="mfma", achieved=round(flops[name] / (avg * 1e-3) / 1e12, 1), unit="TFLOP/s")
+            e["frac"] = round(e["achieved"] / PEAK_BF16_TFLOPS, 4)
+        elif name in byts:
+            e.update(bound="hbm", achieved=round(byts[name] / (avg * 1e-3) / 1e9, 1), unit="GB/s")
+            e["frac"] = round(e["achieved"] / PEAK_HBM_GBS, 4)
+        kernels[name] = e
+    roof = None
+    if "gemm_gate_up" in kernels:
+        k = kernels["gemm_gate_up"]
+        roof = {"bound": "mfma", "kernel": "k_gemm_bf16<EPI_SWIGLU> (gate|up projection + SwiGLU)",
+                "achieved": k["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": k["frac"],
+                "traffic": None, "avg_ms": k["avg_ms"], "flops_per_launch": flops["gemm_gate_up"]}
+    fwd_flops = nl * (flops["gemm_qkv"] + flops["gemm_out"] + flops["gemm_gate_up"] + flops["gemm_down"]
+                      + flops["attention"]) + flops["gemm_lm_head"]
+
+    res = {"metric": "verified image tokens/sec (1 GPU) per verify step", "value": round(M / (ms_per_step * 1e-3), 1),
+           "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 3),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": m["dtype"], "data": "synthetic",
+           "config": {"workload": "%s: %s decoder, B=%d, draft block L=%d of a %dx%d grid (last block, P=%d cache rows), "
+                                  "V=%d, radius %d, sigma %.2g" % (c["name"], c["model_name"], B, L, c["H"], c["W"], P, V,
+                                                                    c["radius"], sigma),
+                      "acceptance_rate": round(acc_rate, 4), "marked_fraction": round(marked, 4)},
+           "step_tflops": round(fwd_flops / (ms_per_step * 1e-3) / 1e12, 1),
+           "step_frac_of_bf16_peak": round(fwd_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+           "roofline": roof, "kernels": kernels}
+    if a.no_cpu_baseline:
+        res["cpu_baseline"] = None
+    else:
+        log("timing the CPU oracle on a bounded sample ...")
+        del ctx
+        res["cpu_baseline"] = cpu_baseline(c, w, cos, sin, seed)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,228 @@
+/*
+ * libmulo -- the parallel verification step of Multi-Scale Local Speculative
+ * Decoding (MuLo-SD) for autoregressive image generation, for one AMD MI355X
+ * (gfx950).  Plain C ABI: no C++ or torch types cross this boundary.
+ *
+ * One verification step (supplementary Alg. 1, Steps 2-5, with the rejected
+ * neighbourhoods re-drawn in one shot):
+ *   Step 2  up-sample the low-resolution draft onto the target grid   (Sec. 3.2)
+ *   Step 3  one pass of the target decoder over the drafted block against the
+ *           KV cache of the prefix                                   (Sec. 3.2)
+ *   Step 4  speculative accept test  min(1, p/q)  per position   (Sec. 3.1, Eq. 1;
+ *           pooled numerator of Eq. 3 when a neighbour table is given)
+ *   Step 5  local expansion: mark the radius-l neighbourhood of every rejected
+ *           position, nothing before the first rejection, no raster-order cut
+ *                                                              (Sec. 3.3, Eq. 6-7)
+ *   then    residual resampling  norm(max(0, p - q))  of the marked positions
+ *                                                              (Sec. 3.1, Eq. 2)
+ *
+ * Conventions that hold for every entry point
+ *   - "device pointer" = memory on the GPU the context was created on, owned by
+ *     the caller, at least 16-byte aligned, valid until the stream work of the
+ *     call has finished.  "host pointer" = ordinary process memory, read during
+ *     the call only.
+ *   - All work is enqueued on the HIP stream given to mulo_create; nothing
+ *     synchronises with the host.  Outputs are valid once the caller has
+ *     synchronised that stream.  A context is not thread-safe.
+ *   - Every argument is checked before anything is launched; on an error
+ *     nothing has been written.  No entry point prints, throws or aborts.
+ *   - Token grids are raster order: position u of an H x W grid sits at row
+ *     u / W, column u % W.  A draft block is L consecutive positions starting at
+ *     n0, both whole multiples of W (the drafter proposes whole rows, Sec. 3.2).
+ */
+#ifndef MULO_H
+#define MULO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MULO_API __attribute__((visibility("default")))
+
+typedef struct mulo_ctx mulo_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    MULO_OK = 0,
+    MULO_ERR_NULL = 1,        /* a required pointer is NULL */
+    MULO_ERR_SHAPE = 2,       /* sizes inconsistent with each other or with the context */
+    MULO_ERR_RANGE = 3,       /* a scalar outside its allowed range */
+    MULO_ERR_ALLOC = 4,       /* device memory for the workspace could not be obtained */
+    MULO_ERR_HIP = 5,         /* a HIP call or a launch failed */
+    MULO_ERR_UNSUPPORTED = 6  /* valid in principle, not handled by these kernels */
+} mulo_status;
+
+typedef enum { MULO_F32 = 0, MULO_BF16 = 1 } mulo_dtype;
+
+/* Decoder dimensions (a pre-norm Llama-style decoder: RMSNorm, rotary multi-head
+ * attention with n_heads * head_dim == d_model, SwiGLU feed-forward, no biases).
+ * max_block is the largest draft block L, max_batch the largest batch B and
+ * max_seq the number of cache rows per sequence (prefix + image tokens).
+ * Limits: head_dim 64 or 128 for MULO_BF16; d_model a multiple of 128, d_ffn of 64,
+ * max_seq of 8 and max_block of 4 for MULO_BF16; vocab a multiple of 4 and at most 262144. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int32_t max_batch, max_seq, max_block;
+    int32_t dtype;   /* mulo_dtype: type of weights, activations and KV cache */
+    float rms_eps;
+} mulo_model_cfg;
+
+/* Target weights, device pointers in the model dtype, row-major [out, in]
+ * (y = x W^T).  The library keeps these pointers (it makes no copy): they must
+ * stay valid and unchanged until mulo_destroy.
+ *   embed [vocab, d]   attn_norm, ffn_norm [n_layers, d]   final_norm [d]
+ *   wq, wk, wv, wo [n_layers, d, d]   w_gate, w_up [n_layers, f, d]
+ *   w_down [n_layers, d, f]   lm_head [vocab, d]
+ * rope_cos / rope_sin: float32 [max_seq, head_dim / 2]; row = absolute cache
+ * position, column m rotates the pair (2m, 2m+1) of every head. */
+typedef struct {
+    const void *embed, *attn_norm, *wq, *wk, *wv, *wo, *ffn_norm, *w_gate, *w_up, *w_down,
+        *final_norm, *lm_head;
+    const float *rope_cos, *rope_sin;
+} mulo_weights;
+
+/* KV cache of the target, device memory of the caller in the model dtype.
+ *   k: [n_layers, max_batch, n_heads, max_seq, head_dim]   (position-major rows)
+ *   v: [n_layers, max_batch, n_heads, head_dim, max_seq]   (stored transposed, so
+ *      that the attention kernel reads keys contiguously for its second product)
+ * Rows [0, P) must hold the prefix; mulo_verify_forward writes rows [P, P+L). */
+typedef struct {
+    void *k, *v;
+} mulo_kv;
+
+/* Parameters of the decision stage (host struct).
+ *   H, W        target grid; n0 first position of the block; L block length
+ *   radius      l of Eq. 6 (>= 0); -1 selects the raster-scan rule of standard
+ *               speculative decoding (everything from the first rejection on)
+ *   expand      number of dilations by `radius` (1 = Eq. 6-7 as printed,
+ *               0 = only the rejected positions themselves)
+ *   pool_k,nbr  codebook-neighbour pooling of Eq. 3: nbr is a device pointer to
+ *               int32 [vocab, pool_k] with nbr[x][0] == x; pool_k == 1 (nbr may be
+ *               NULL) is the plain test of Eq. 1
+ *   resample_mode 0: every marked position draws from the residual of Eq. 2;
+ *               1: rejected positions draw from the residual, positions marked
+ *               only by expansion draw from p
+ *   seed, rng_counter  Philox4x32-10 key and per-step counter; position t of
+ *               batch element b uses counter words (t, b, counter_lo,
+ *               stream << 24 | counter_hi & 0xffffff), stream 0 for the accept
+ *               uniform u = (word0 >> 8) * 2^-24 and 1 for the sampler word. */
+typedef struct {
+    int32_t H, W, n0, L;
+    int32_t radius, expand;
+    int32_t pool_k;
+    const int32_t *nbr;
+    int32_t resample_mode;
+    uint64_t seed, rng_counter;
+} mulo_step_params;
+
+/* Static description of a status code; never NULL. */
+MULO_API const char *mulo_status_string(mulo_status s);
+
+/* Pure host-side checks (no GPU needed), also run by the entry points below. */
+MULO_API mulo_status mulo_check_model_cfg(const mulo_model_cfg *cfg);
+MULO_API mulo_status mulo_check_step_params(const mulo_model_cfg *cfg, int32_t B, const mulo_step_params *p);
+
+/* Device bytes mulo_create will allocate for its workspace (0 on a bad cfg). */
+MULO_API uint64_t mulo_workspace_bytes(const mulo_model_cfg *cfg);
+
+/* Create a context on the current HIP device.  cfg and w are host structs
+ * (copied); w's members are device pointers (kept, see above).  hip_stream is a
+ * hipStream_t (NULL = the default stream).  Allocates the workspace once; no
+ * later call allocates.  *out is set only on MULO_OK. */
+MULO_API mulo_status mulo_create(const mulo_model_cfg *cfg, const mulo_weights *w, void *hip_stream,
+                        mulo_ctx **out);
+MULO_API void mulo_destroy(mulo_ctx *ctx); /* NULL is allowed */
+
+/* Step 2 (Sec. 3.2; Alg. 1 Step 2).  Weight-free up-sampling by replication:
+ * every low-resolution cell (I, J) of the h x w draft grid emits its r x r
+ * children on the (r h) x (r w) grid, and a child's draft distribution is its
+ * parent's.
+ *   draft        device float32 [B, h*w, vocab]: draft logits, or probabilities
+ *                when input_is_probs != 0
+ *   draft_tokens device int32 [B, h*w]
+ *   tokens_hi    device int32 [B, r*h * r*w]        (out)
+ *   q_lo         device float32 [B, h*w, vocab]     (out) softmax(draft), or a copy;
+ *                may alias `draft` when input_is_probs != 0
+ *   q_row        device int32 [r*h * r*w]           (out) parent row of each position
+ *   q_hi         device float32 [B, r*h*r*w, vocab] (out) or NULL: materialised rows
+ * Errors: NULL -> MULO_ERR_NULL; B, h, w, r < 1 -> MULO_ERR_RANGE. */
+MULO_API mulo_status mulo_upsample_draft(mulo_ctx *ctx, int32_t B, int32_t h, int32_t w, int32_t r,
+                                const float *draft, int32_t input_is_probs,
+                                const int32_t *draft_tokens, int32_t *tokens_hi, float *q_lo,
+                                int32_t *q_row, float *q_hi);
+
+/* Step 3 (Sec. 3.2; Alg. 1 Step 3).  One forward pass of the target over L
+ * inputs per sequence against cache rows [0, P); logits[b, j, :] is the
+ * next-token logit vector AFTER input j.  Writes cache rows [P, P+L).
+ *   in_tokens  device int32 [B, L] (ids outside [0, vocab) are clamped)
+ *   in_embeds  device, model dtype [B, L, d], or NULL; when given it replaces
+ *              the embedding lookup (conditioning prefixes)
+ *   logits     device float32 [B, L, vocab] (out)
+ * Errors: B > max_batch, L > max_block, P + L > max_seq -> MULO_ERR_SHAPE. */
+MULO_API mulo_status mulo_verify_forward(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int32_t L, int32_t P,
+                                const int32_t *in_tokens, const void *in_embeds, float *logits);
+
+/* Steps 4-5 and the residual re-draw (Sec. 3.1 Eq. 1-3; Sec. 3.3 Eq. 6-7).
+ *   logits       device float32 [B, L, vocab]  target logits of the block
+ *   q            device float32 draft probabilities; row of position t of batch
+ *                b starts at q + b * q_batch_stride + row(t) * vocab, where
+ *                row(t) = q_row[t], or t when q_row is NULL
+ *   draft_tokens device int32 [B, L]  x~ on the target grid
+ *   tokens_out   device int32 [B, L]  (out) x~ where unmarked, re-drawn where marked
+ *   accept, mask device uint8 [B, L]  (out) 1 = accepted / 1 = marked (R_X)
+ *   t0           device int32 [B]     (out) first rejected position, L if none
+ *   stats        device int32 [B, 4]  (out) accepted, rejected, marked, near ties
+ *                (|pbar - u q| < 1e-4 q)
+ *   p_probs      device float32 [B, L, vocab] (out) or NULL: softmax(logits) */
+MULO_API mulo_status mulo_accept_local_resample(mulo_ctx *ctx, int32_t B, const mulo_step_params *p,
+                                       const float *logits, const float *q, const int32_t *q_row,
+                                       int64_t q_batch_stride, const int32_t *draft_tokens,
+                                       int32_t *tokens_out, uint8_t *accept, uint8_t *mask,
+                                       int32_t *t0, int32_t *stats, float *p_probs);
+
+/* The whole step for one block: up-sample the h_blk x w low-resolution rows
+ * behind the block (h_blk * r * w * r == L), run the target over the inputs
+ * [prev, x~_0 .. x~_{L-2}] so that logit row j is p for draft position j, then
+ * decide and re-draw.  Cache rows [P, P+L) are written; rows after the first
+ * rejection are stale afterwards and P is never advanced (the caller commits).
+ *   draft        device float32 [B, h_blk*w, vocab] logits (or probabilities)
+ *   draft_tokens device int32 [B, h_blk*w]
+ *   prev_tokens  device int32 [B]  last committed (or last prefix) token
+ *   tokens_hi    device int32 [B, L] (out) or NULL: the up-sampled draft x~
+ *   logits       device float32 [B, L, vocab] (out) or NULL
+ *   other outputs as in mulo_accept_local_resample. */
+MULO_API mulo_status mulo_verify_step(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int32_t P,
+                             const mulo_step_params *p, int32_t h_blk, int32_t w, int32_t r,
+                             const float *draft, int32_t input_is_probs,
+                             const int32_t *draft_tokens, const int32_t *prev_tokens,
+                             int32_t *tokens_out, uint8_t *accept, uint8_t *mask, int32_t *t0,
+                             int32_t *stats, int32_t *tokens_hi, float *logits);
+
+/* Optional per-kernel timing (measurement aid, not part of the method).  While
+ * enabled, every kernel launch of the entry points above is bracketed by a pair
+ * of HIP events on the context's stream.  mulo_profile_read synchronises the
+ * stream, adds up the elapsed time and the launch count per kernel class since
+ * the last read, and clears them.  ms and launches are host arrays of
+ * MULO_PROF_N entries.  At most 16384 launches are recorded between two reads. */
+enum {
+    MULO_PROF_GEMM_QKV = 0,   /* QKV projection + rotary + cache append */
+    MULO_PROF_GEMM_OUT = 1,   /* attention output projection + residual */
+    MULO_PROF_GEMM_GATE_UP = 2, /* gate|up projection + SwiGLU */
+    MULO_PROF_GEMM_DOWN = 3,  /* down projection + residual */
+    MULO_PROF_GEMM_LM_HEAD = 4,
+    MULO_PROF_ATTENTION = 5,
+    MULO_PROF_NORM_EMBED = 6, /* embedding lookup, RMSNorm */
+    MULO_PROF_UPSAMPLE = 7,   /* draft softmax, token replication, input shift */
+    MULO_PROF_ACCEPT = 8,     /* target softmax statistics + accept test */
+    MULO_PROF_MASK_SAMPLE = 9, /* neighbourhood mask + residual draw */
+    MULO_PROF_OTHER = 10,     /* float32-path helpers */
+    MULO_PROF_N = 11
+};
+MULO_API mulo_status mulo_profile(mulo_ctx *ctx, int32_t enable);
+MULO_API mulo_status mulo_profile_read(mulo_ctx *ctx, float *ms, int32_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MULO_H */

@@ -87,9 +87,10 @@ class DecoderOracle:
         return t.to(torch.float64)
 
     @torch.no_grad()
-    def forward(self, tokens, P, embeds=None):
+    def forward(self, tokens, P, embeds=None, taps=None):
         """tokens: int [B, L]; P: number of valid cache rows; writes cache rows
-        P .. P+L-1; returns float64 logits [B, L, V]."""
+        P .. P+L-1; returns float64 logits [B, L, V].  taps: optional list that
+        receives a copy of the residual stream entering every layer."""
         cfg = self.cfg
         nl, d, nh, dh = cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
         eps = cfg.get("rms_eps", 1e-5)
@@ -104,6 +105,8 @@ class DecoderOracle:
         pos_q = torch.arange(P, S)[:, None]
         visible = torch.arange(S)[None, :] <= pos_q                  # key s visible to query j iff s <= P + j
         for l in range(nl):
+            if taps is not None:
+                taps.append(x.clone())
             xh = self.rb(rmsnorm(x, self._w("attn_norm", l), eps))
             q = (xh @ self._w("wq", l).T).reshape(B, L, nh, dh)
             k = (xh @ self._w("wk", l).T).reshape(B, L, nh, dh)

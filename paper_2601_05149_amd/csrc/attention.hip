@@ -1,0 +1,295 @@
+// Causal attention of the drafted block over prefix + block (Alg. 1 Step 3: the
+// j-th conditional sees cache rows 0 .. P+j).
+//
+// bf16 path: flash-style, one workgroup of 4 wavefronts per (128 queries, head,
+// sequence); K and V^T tiles of 64 keys are staged through LDS (double buffered)
+// and shared by the 4 wavefronts; each wavefront owns 32 queries and computes
+// S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so that a lane
+// owns ONE query: the softmax row reductions stay inside the lane (plus one
+// cross-half shuffle), and the exponentiated scores are already laid out as the
+// B operand of the second product.  The K rows are fetched in a permuted order
+// (bits 2 and 3 of the row index swapped) so that a lane's accumulators cover 8
+// consecutive keys, which is what lets V^T be read with 16-byte LDS loads.
+// float32 path (small configuration): one workgroup per query row.
+#include <hip/hip_bf16.h>
+
+#include "mulo_internal.h"
+
+namespace mulo {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __hip_bfloat16 bf16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int BQ = 128, BKV = 64, NTH = 256;
+constexpr float LOG2E = 1.4426950408889634f;
+
+struct AttnArgs {
+    const bf16* q;    // [B, nh, L, dh]
+    const bf16* kc;   // [nl, maxB, nh, S, dh]
+    const bf16* vc;   // [nl, maxB, nh, dh, S]
+    bf16* out;        // [B*L, nh*dh]
+    int B, L, P, nh, max_seq, max_batch, layer;
+    float scale_log2;  // log2(e) / sqrt(dh)
+};
+
+template <int DH>
+__global__ __launch_bounds__(NTH) void k_attn_bf16(const AttnArgs a) {
+    constexpr int KS = DH + 8;     // K tile row stride (bf16)
+    constexpr int VS = BKV + 8;    // V^T tile row stride
+    constexpr int NKK = DH / 16;   // k-steps of the first product
+    constexpr int NDB = DH / 32;   // 32-row blocks of O^T
+    constexpr int LK = BKV * (DH / 8) / NTH, LV = DH * (BKV / 8) / NTH;  // 16-byte chunks per lane
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16* sK = reinterpret_cast<bf16*>(smem);   // [2][BKV][KS]
+    bf16* sV = sK + 2 * BKV * KS;               // [2][DH][VS]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+    const int j0 = blockIdx.x * BQ, hd = blockIdx.y, b = blockIdx.z;
+    const int64_t hb = ((int64_t)a.layer * a.max_batch + b) * a.nh + hd;
+    const bf16* kbase = a.kc + hb * a.max_seq * DH;
+    const bf16* vbase = a.vc + hb * DH * a.max_seq;
+
+    // this lane's query (clamped for the ragged last tile; such lanes do not store)
+    const int jq_raw = j0 + wave * 32 + l32;
+    const int jq = jq_raw < a.L ? jq_raw : a.L - 1;
+    const int qpos = a.P + jq;
+    const int wave_jmin = j0 + wave * 32;
+    int wave_jmax = wave_jmin + 31;
+    wave_jmax = wave_jmax < a.L ? wave_jmax : a.L - 1;
+    const bool wave_live = wave_jmin < a.L;
+
+    bf16x8 qf[NKK];
+    {
+        const bf16* qp = a.q + (((int64_t)b * a.nh + hd) * a.L + jq) * DH + lh * 8;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+    }
+
+    int blk_jmax = j0 + BQ - 1;
+    blk_jmax = blk_jmax < a.L ? blk_jmax : a.L - 1;
+    const int kmax_blk = a.P + blk_jmax;   // last key any query of this workgroup may see
+    const int n_tiles = kmax_blk / BKV + 1;
+
+    u32x4 rk[LK], rv[LV];
+    auto gload = [&](int t) {
+        const int kv0 = t * BKV;
+#pragma unroll
+        for (int i = 0; i < LK; ++i) {
+            const int c = tid + i * NTH, row = c / (DH / 8), col = (c % (DH / 8)) * 8;
+            int key = kv0 + row;
+            key = key < a.max_seq ? key : a.max_seq - 1;
+            rk[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * DH + col);
+        }
+#pragma unroll
+        for (int i = 0; i < LV; ++i) {
+            const int c = tid + i * NTH, row = c / (BKV / 8), col = (c % (BKV / 8)) * 8;
+            int key = kv0 + col;
+            const int kc_ = key + 8 <= a.max_seq ? key : a.max_seq - 8;
+            rv[i] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)row * a.max_seq + kc_);
+            // cache columns past the last visible key may be uninitialised memory: their
+            // probabilities are 0, and 0 * NaN must not reach the accumulators
+            if (kv0 + BKV - 1 > kmax_blk) {
+                auto keep = [&](int e) -> uint32_t { return key + e <= kmax_blk ? 0xFFFFu : 0u; };
+                rv[i].x &= keep(0) | (keep(1) << 16);
+                rv[i].y &= keep(2) | (keep(3) << 16);
+                rv[i].z &= keep(4) | (keep(5) << 16);
+                rv[i].w &= keep(6) | (keep(7) << 16);
+            }
+        }
+    };
+    auto sstore = [&](int buf) {
+        bf16* k = sK + buf * BKV * KS;
+        bf16* v = sV + buf * DH * VS;
+#pragma unroll
+        for (int i = 0; i < LK; ++i) {
+            const int c = tid + i * NTH, row = c / (DH / 8), col = (c % (DH / 8)) * 8;
+            *reinterpret_cast<u32x4*>(k + row * KS + col) = rk[i];
+        }
+#pragma unroll
+        for (int i = 0; i < LV; ++i) {
+            const int c = tid + i * NTH, row = c / (BKV / 8), col = (c % (BKV / 8)) * 8;
+            *reinterpret_cast<u32x4*>(v + row * VS + col) = rv[i];
+        }
+    };
+
+    f32x16 o[NDB];
+#pragma unroll
+    for (int i = 0; i < NDB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+    float m_run = -__builtin_huge_valf(), l_run = 0.f;
+
+    // MFMA row rho of a K block is fed key kperm(rho): bits 2 and 3 swapped
+    const int kperm = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        if (t + 1 < n_tiles) gload(t + 1);
+        const int kv0 = t * BKV;
+        if (wave_live && kv0 <= a.P + wave_jmax) {
+            const bf16* k = sK + (t & 1) * BKV * KS;
+            const bf16* v = sV + (t & 1) * DH * VS;
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+                const bf16* kr = k + (kb * 32 + kperm) * KS + lh * 8;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk)
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8*>(kr + kk * 16), qf[kk], s[kb], 0, 0, 0);
+            }
+            // accumulator r of block kb holds key kv0 + kb*32 + 16*(r/8) + 8*lh + r%8 for query l32
+            const bool need_mask = kv0 + BKV - 1 > a.P + wave_jmin;
+            float mx = -__builtin_huge_valf();
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float x = s[kb][r] * a.scale_log2;
+                    if (need_mask) {
+                        const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+                        x = key <= qpos ? x : -__builtin_huge_valf();
+                    }
+                    s[kb][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            float ps = 0.f;
+            bf16x8 pf[4];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_new);
+                    ps += p;
+                    pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
+                }
+            l_run = l_run * alpha + ps;
+#pragma unroll
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+            // O^T += V^T P^T : k-step ks covers keys kv0 + 16 ks .. +15
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+                for (int i = 0; i < NDB; ++i) {
+                    const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v + (i * 32 + l32) * VS + ks * 16 + lh * 8);
+                    o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], o[i], 0, 0, 0);
+                }
+            }
+        }
+        if (t + 1 < n_tiles) sstore((t + 1) & 1);
+        __syncthreads();
+    }
+
+    l_run += __shfl_xor(l_run, 32);
+    if (jq_raw < a.L) {
+        const float inv = 1.0f / l_run;
+        bf16* op = a.out + ((int64_t)b * a.L + jq) * (a.nh * DH) + hd * DH;
+#pragma unroll
+        for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[i][g4 * 4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + i * 32 + g4 * 8 + lh * 4) = w;
+            }
+    }
+}
+
+// float32: one workgroup per (query j, head, sequence); scores live in LDS.
+__global__ __launch_bounds__(256) void k_attn_f32(const float* __restrict__ q, const float* __restrict__ kc,
+                                                  const float* __restrict__ vc, float* __restrict__ out, int L,
+                                                  int P, int nh, int dh, int max_seq, int max_batch, int layer) {
+    extern __shared__ float sc[];   // [dh] query, then [P + j + 1] scores
+    __shared__ float red[4];
+    const int j = blockIdx.x, hd = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int n = P + j + 1;
+    float* qs = sc;
+    float* s = sc + dh;
+    const int64_t hb = ((int64_t)layer * max_batch + b) * nh + hd;
+    const float* kb = kc + hb * max_seq * dh;
+    const float* vb = vc + hb * dh * max_seq;
+    for (int c = tid; c < dh; c += 256) qs[c] = q[(((int64_t)b * nh + hd) * L + j) * dh + c];
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)dh);
+    float mx = -__builtin_huge_valf();
+    for (int t = tid; t < n; t += 256) {
+        float acc = 0.f;
+        for (int c = 0; c < dh; ++c) acc += qs[c] * kb[(int64_t)t * dh + c];
+        acc *= scale;
+        s[t] = acc;
+        mx = fmaxf(mx, acc);
+    }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float sum = 0.f;
+    for (int t = tid; t < n; t += 256) {
+        const float e = expf(s[t] - mx);
+        s[t] = e;
+        sum += e;
+    }
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((tid & 63) == 0) red[tid >> 6] = sum;
+    __syncthreads();
+    sum = (red[0] + red[1]) + (red[2] + red[3]);
+    for (int c = tid; c < dh; c += 256) {
+        float acc = 0.f;
+        for (int t = 0; t < n; ++t) acc += s[t] * vb[(int64_t)c * max_seq + t];
+        out[((int64_t)b * L + j) * (nh * dh) + hd * dh + c] = acc / sum;
+    }
+}
+
+template <int DH>
+void run_attn(const AttnArgs& a, hipStream_t st) {
+    auto kern = k_attn_bf16<DH>;
+    const size_t lds = (size_t)2 * (BKV * (DH + 8) + DH * (BKV + 8)) * sizeof(bf16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((a.L + BQ - 1) / BQ, a.nh, a.B), dim3(NTH), lds, st, a);
+}
+
+}  // namespace
+
+void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B, int L,
+                           int P, int n_heads, int head_dim, int max_seq, int max_batch, int layer,
+                           hipStream_t st) {
+    AttnArgs a{};
+    a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
+    a.B = B; a.L = L; a.P = P; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
+    a.scale_log2 = LOG2E / sqrtf((float)head_dim);
+    if (head_dim == 128) run_attn<128>(a, st);
+    else run_attn<64>(a, st);
+}
+
+void launch_attention_f32(const float* q, const float* k_cache, const float* v_cache, float* out,
+                          float* scratch, int B, int L, int P, int n_heads, int head_dim, int max_seq,
+                          int max_batch, int layer, hipStream_t st) {
+    (void)scratch;
+    const size_t lds = (size_t)(head_dim + P + L) * sizeof(float);
+    hipLaunchKernelGGL(k_attn_f32, dim3(L, n_heads, B), dim3(256), lds, st, q, k_cache, v_cache, out, L, P,
+                       n_heads, head_dim, max_seq, max_batch, layer);
+}
+
+}  // namespace mulo

@@ -1,0 +1,445 @@
+// Decision stage of the verification step: draft up-sampling (Sec. 3.2, Step 2),
+// the speculative accept test (Sec. 3.1, Eq. 1 / Eq. 3), local expansion
+// (Sec. 3.3, Eq. 6-7) and residual resampling (Sec. 3.1, Eq. 2).
+//
+// All of it is bound by HBM reads of [rows, V] float32 matrices: one workgroup of
+// 256 lanes owns one row, keeps it in registers (V <= 16384) and reduces over the
+// codebook with wavefront shuffles, so every logit is read from memory once in
+// the accept pass and once more (with the draft row) only for marked positions.
+#include "mulo_internal.h"
+
+namespace mulo {
+
+namespace {
+
+constexpr int TPB = 256;
+constexpr int WAVES = TPB / 64;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float NEAR_TIE = 1e-4f;
+constexpr int MAX_CHUNKS = 1024;  // 256 codebook entries per chunk -> V <= 262144
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+// inclusive prefix sum over the 64 lanes of a wavefront
+__device__ __forceinline__ unsigned long long wave_scan_u64(unsigned long long v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        unsigned long long n = __shfl_up(v, o);
+        if (lane >= o) v += n;
+    }
+    return v;
+}
+
+// Fixed-order block reductions (run-to-run deterministic).
+__device__ __forceinline__ float block_max(float v, float* red) {
+    v = wave_max(v);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int i = 1; i < WAVES; ++i) r = fmaxf(r, red[i]);
+    return r;
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int i = 1; i < WAVES; ++i) r += red[i];
+    return r;
+}
+
+// exp(z - m) with one hardware exp2; no contraction so every kernel that
+// evaluates it gets the same bits.
+__device__ __forceinline__ float expm(float z, float m) {
+    return __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z, m), LOG2E));
+}
+__device__ __forceinline__ float prob(float z, float m, float inv) {
+    return __fmul_rn(expm(z, m), inv);
+}
+
+// Philox4x32-10 (Salmon et al., SC'11), word 0 of the output block.
+__device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    return c0;
+}
+
+// ---- a row of V floats held by one workgroup -------------------------------
+// NV4 > 0: registers (V <= 1024 * NV4); NV4 == 0: re-read from memory (L2) per pass.
+template <int NV4>
+struct RowRegs {
+    float4 v[NV4 > 0 ? NV4 : 1];
+};
+
+template <int NV4>
+__device__ __forceinline__ void row_stats(const float* __restrict__ src, int V, RowRegs<NV4>& rr,
+                                          float* red, float& m, float& inv) {
+    const int nv4 = V >> 2, tid = threadIdx.x;
+    const float4* s4 = reinterpret_cast<const float4*>(src);
+    const float NEG = -__builtin_huge_valf();
+    float mx = NEG;
+    if constexpr (NV4 > 0) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            const int idx = i * TPB + tid;
+            rr.v[i] = idx < nv4 ? s4[idx] : make_float4(NEG, NEG, NEG, NEG);
+            mx = fmaxf(fmaxf(mx, fmaxf(rr.v[i].x, rr.v[i].y)), fmaxf(rr.v[i].z, rr.v[i].w));
+        }
+    } else {
+        for (int idx = tid; idx < nv4; idx += TPB) {
+            const float4 t = s4[idx];
+            mx = fmaxf(fmaxf(mx, fmaxf(t.x, t.y)), fmaxf(t.z, t.w));
+        }
+    }
+    m = block_max(mx, red);
+    float s = 0.f;
+    if constexpr (NV4 > 0) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            rr.v[i].x = expm(rr.v[i].x, m); rr.v[i].y = expm(rr.v[i].y, m);
+            rr.v[i].z = expm(rr.v[i].z, m); rr.v[i].w = expm(rr.v[i].w, m);
+            s += (rr.v[i].x + rr.v[i].y) + (rr.v[i].z + rr.v[i].w);
+        }
+    } else {
+        for (int idx = tid; idx < nv4; idx += TPB) {
+            const float4 t = s4[idx];
+            s += (expm(t.x, m) + expm(t.y, m)) + (expm(t.z, m) + expm(t.w, m));
+        }
+    }
+    s = block_sum(s, red);
+    inv = 1.0f / s;
+}
+
+template <int NV4>
+__device__ __forceinline__ void row_write_probs(const float* __restrict__ src, float* __restrict__ dst,
+                                                int V, const RowRegs<NV4>& rr, float m, float inv) {
+    const int nv4 = V >> 2, tid = threadIdx.x;
+    float4* d4 = reinterpret_cast<float4*>(dst);
+    if constexpr (NV4 > 0) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            const int idx = i * TPB + tid;
+            if (idx < nv4)
+                d4[idx] = make_float4(__fmul_rn(rr.v[i].x, inv), __fmul_rn(rr.v[i].y, inv),
+                                      __fmul_rn(rr.v[i].z, inv), __fmul_rn(rr.v[i].w, inv));
+        }
+    } else {
+        const float4* s4 = reinterpret_cast<const float4*>(src);
+        for (int idx = tid; idx < nv4; idx += TPB) {
+            const float4 t = s4[idx];
+            d4[idx] = make_float4(prob(t.x, m, inv), prob(t.y, m, inv), prob(t.z, m, inv),
+                                  prob(t.w, m, inv));
+        }
+    }
+}
+
+// ---- Step 2: softmax of the draft logits, one workgroup per low-res cell ----
+template <int NV4>
+__global__ __launch_bounds__(TPB) void k_softmax_rows(const float* __restrict__ in,
+                                                      float* __restrict__ out, int V) {
+    __shared__ float red[WAVES];
+    const int64_t row = blockIdx.x;
+    RowRegs<NV4> rr;
+    float m, inv;
+    row_stats<NV4>(in + row * V, V, rr, red, m, inv);
+    row_write_probs<NV4>(in + row * V, out + row * V, V, rr, m, inv);
+}
+
+__global__ __launch_bounds__(TPB) void k_copy(const float4* __restrict__ in, float4* __restrict__ out,
+                                              int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < n4; i += (int64_t)gridDim.x * TPB)
+        out[i] = in[i];
+}
+
+// x~[b, (rI+a) W + rJ+c] = y~[b, I w + J];  q_row[u] = (i_u / r) w + j_u / r
+__global__ __launch_bounds__(TPB) void k_upsample_tokens(const int32_t* __restrict__ lo,
+                                                         int32_t* __restrict__ hi,
+                                                         int32_t* __restrict__ q_row, int B, int h,
+                                                         int w, int r) {
+    const int W = w * r, T = h * r * W;
+    const int64_t gid = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (gid >= (int64_t)B * T) return;
+    const int b = gid / T, u = gid % T;
+    const int par = ((u / W) / r) * w + (u % W) / r;
+    hi[gid] = lo[(int64_t)b * h * w + par];
+    if (b == 0) q_row[u] = par;
+}
+
+// q_hi[b, u, :] = q_lo[b, q_row[u], :]
+__global__ __launch_bounds__(TPB) void k_gather_rows(const float* __restrict__ q_lo,
+                                                     const int32_t* __restrict__ q_row,
+                                                     float* __restrict__ q_hi, int n_lo, int n_hi,
+                                                     int V) {
+    const int u = blockIdx.x, b = blockIdx.y;
+    const float4* s = reinterpret_cast<const float4*>(q_lo + ((int64_t)b * n_lo + q_row[u]) * V);
+    float4* d = reinterpret_cast<float4*>(q_hi + ((int64_t)b * n_hi + u) * V);
+    for (int i = threadIdx.x; i < (V >> 2); i += TPB) d[i] = s[i];
+}
+
+__global__ void k_shift_inputs(const int32_t* __restrict__ prev, const int32_t* __restrict__ hi,
+                               int32_t* __restrict__ inp, int B, int L) {
+    const int64_t gid = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (gid >= (int64_t)B * L) return;
+    const int b = gid / L, j = gid % L;
+    inp[gid] = j == 0 ? prev[b] : hi[gid - 1];
+}
+
+// ---- Step 4: softmax statistics + accept test, one workgroup per position ---
+__global__ void k_decide_init(int32_t* t0, int32_t* stats, int B, int L) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B) t0[i] = L;
+    if (i < 4 * B) stats[i] = 0;
+}
+
+__device__ __forceinline__ int clamp_tok(int t, int V) { return t < 0 ? 0 : (t >= V ? V - 1 : t); }
+
+template <int NV4>
+__global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
+    __shared__ float red[WAVES];
+    const int64_t row = blockIdx.x;
+    const int b = row / a.L, t = row % a.L, tid = threadIdx.x;
+    const float* z = a.logits + row * a.V;
+    RowRegs<NV4> rr;
+    float m, inv;
+    row_stats<NV4>(z, a.V, rr, red, m, inv);
+    if (a.p_probs) row_write_probs<NV4>(z, a.p_probs + row * a.V, a.V, rr, m, inv);
+
+    const int tok = clamp_tok(a.draft_tokens[row], a.V);
+    float pbar;
+    if (a.pool_k <= 1) {
+        pbar = prob(z[tok], m, inv);
+    } else {  // Eq. 3: pooled mass over the codebook neighbours of the draft token
+        float acc = 0.f;
+        for (int i = tid; i < a.pool_k; i += TPB)
+            acc += prob(z[clamp_tok(a.nbr[(int64_t)tok * a.pool_k + i], a.V)], m, inv);
+        pbar = block_sum(acc, red);
+    }
+    if (tid == 0) {
+        const int qr = a.q_row ? a.q_row[t] : t;
+        const float qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
+        const uint32_t w0 = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24, a.key0, a.key1);
+        const float u = (float)(w0 >> 8) * 5.9604644775390625e-08f;  // 2^-24, exact
+        const float uq = __fmul_rn(u, qt);
+        const bool ok = uq < pbar;  // Eq. 1 without the division: u q < pbar
+        a.accept[row] = ok ? 1 : 0;
+        a.rowmax[row] = m;
+        a.rowinv[row] = inv;
+        atomicAdd(&a.stats[b * 4 + (ok ? 0 : 1)], 1);
+        if (!ok) atomicMin(&a.t0[b], t);
+        if (fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, qt)) atomicAdd(&a.stats[b * 4 + 3], 1);
+    }
+}
+
+// ---- Step 5 + Eq. 2: neighbourhood mask, then the residual draw -------------
+__device__ __forceinline__ void weights4(const float4 z, const float4 qv, float m, float inv, bool use_p,
+                                         unsigned long long w[4]) {
+    const float S = 1099511627776.0f;  // 2^40: w * S is exact in float32
+    float p0 = prob(z.x, m, inv), p1 = prob(z.y, m, inv), p2 = prob(z.z, m, inv), p3 = prob(z.w, m, inv);
+    if (!use_p) {
+        p0 = fmaxf(0.f, __fsub_rn(p0, qv.x)); p1 = fmaxf(0.f, __fsub_rn(p1, qv.y));
+        p2 = fmaxf(0.f, __fsub_rn(p2, qv.z)); p3 = fmaxf(0.f, __fsub_rn(p3, qv.w));
+    }
+    w[0] = (unsigned long long)__fmul_rn(p0, S); w[1] = (unsigned long long)__fmul_rn(p1, S);
+    w[2] = (unsigned long long)__fmul_rn(p2, S); w[3] = (unsigned long long)__fmul_rn(p3, S);
+}
+
+__global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
+    __shared__ unsigned long long chunk[MAX_CHUNKS];
+    __shared__ int s_retry;
+    const int64_t row = blockIdx.x;
+    const int b = row / a.L, t = row % a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+    // R_X membership of this position (Eq. 6-7): at or after t0 and within
+    // Chebyshev distance rho of some rejected position of the block.
+    int marked = 0;
+    const int t0 = a.t0[b];
+    if (t >= t0) {
+        if (a.rho < 0) {
+            marked = 1;
+        } else {
+            const int g = a.n0 + t, gi = g / a.W, gj = g % a.W, side = 2 * a.rho + 1;
+            for (int c = tid; c < side * side; c += TPB) {
+                const int ii = gi + c / side - a.rho, jj = gj + c % side - a.rho;
+                if (ii >= 0 && ii < a.H && jj >= 0 && jj < a.W) {
+                    const int tt = ii * a.W + jj - a.n0;
+                    if (tt >= 0 && tt < a.L && a.accept[(int64_t)b * a.L + tt] == 0) marked = 1;
+                }
+            }
+        }
+    }
+    marked = __syncthreads_or(marked);
+    const int draft = clamp_tok(a.draft_tokens[row], a.V);
+    if (tid == 0) {
+        a.mask[row] = marked ? 1 : 0;
+        if (marked) atomicAdd(&a.stats[b * 4 + 2], 1);
+        else a.tokens_out[row] = draft;
+    }
+    if (!marked) return;
+
+    // Residual draw through an integer CDF: W(x) = floor(max(0, p - q) 2^40),
+    // T = (word * tot) >> 32, token = first x whose inclusive prefix exceeds T.
+    const int V = a.V, nv4 = V >> 2, nchunks = (nv4 + 63) >> 6;
+    const float4* z4 = reinterpret_cast<const float4*>(a.logits + row * V);
+    const int qr = a.q_row ? a.q_row[t] : t;
+    const float4* q4 = reinterpret_cast<const float4*>(a.q + b * a.q_batch_stride + (int64_t)qr * V);
+    const float m = a.rowmax[row], inv = a.rowinv[row];
+    bool use_p = (a.resample_mode == 1) && a.accept[row] != 0;
+    const uint32_t word = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24 | (1u << 24),
+                                       a.key0, a.key1);
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        for (int base = 0; base < nv4; base += TPB) {
+            const int idx = base + tid;
+            unsigned long long s = 0;
+            if (idx < nv4) {
+                unsigned long long w[4];
+                weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                s = (w[0] + w[1]) + (w[2] + w[3]);
+            }
+            s = wave_sum_u64(s);
+            const int c = (base >> 6) + wv;
+            if (lane == 0 && c < nchunks) chunk[c] = s;
+        }
+        if (tid == 0) s_retry = 0;
+        __syncthreads();
+        if (wv == 0) {
+            unsigned long long tot = 0;
+            for (int c0 = 0; c0 < nchunks; c0 += 64) tot += (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
+            tot = wave_sum_u64(tot);
+            if (tot == 0) {
+                if (lane == 0) s_retry = 1;  // empty residual: draw from p instead
+            } else {
+                const unsigned long long T = __umul64hi((unsigned long long)word << 32, tot);
+                unsigned long long run = 0, before = 0;
+                int cidx = nchunks - 1;
+                for (int c0 = 0; c0 < nchunks; c0 += 64) {
+                    const unsigned long long v = (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
+                    const unsigned long long incl = wave_scan_u64(v, lane) + run;
+                    const unsigned long long hit = __ballot(incl > T);
+                    if (hit) {
+                        const int f = __ffsll((long long)hit) - 1;
+                        cidx = c0 + f;
+                        before = __shfl(incl - v, f);
+                        break;
+                    }
+                    run = __shfl(incl, 63);
+                }
+                // inside the chunk: 64 lanes x 4 entries, same weights as above
+                const int idx = cidx * 64 + lane;
+                unsigned long long w[4] = {0, 0, 0, 0};
+                if (idx < nv4) weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                const unsigned long long s = (w[0] + w[1]) + (w[2] + w[3]);
+                const unsigned long long incl = wave_scan_u64(s, lane) + before;
+                const unsigned long long hit = __ballot(incl > T);
+                const int f = hit ? __ffsll((long long)hit) - 1 : 63;
+                if (lane == f) {
+                    unsigned long long cum = incl - s;
+                    int tok = draft;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        cum += w[e];
+                        if (cum > T) { tok = idx * 4 + e; break; }
+                    }
+                    a.tokens_out[row] = clamp_tok(tok, V);
+                }
+            }
+        }
+        __syncthreads();
+        if (!s_retry || use_p) break;
+        use_p = true;
+        __syncthreads();
+    }
+}
+
+template <int NV4>
+void softmax_rows_inst(const float* in, float* out, int64_t rows, int V, hipStream_t st) {
+    hipLaunchKernelGGL(k_softmax_rows<NV4>, dim3((unsigned)rows), dim3(TPB), 0, st, in, out, V);
+}
+template <int NV4>
+void accept_inst(const DecideArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(k_accept<NV4>, dim3((unsigned)(a.B * a.L)), dim3(TPB), 0, st, a);
+}
+
+}  // namespace
+
+void launch_softmax_rows(const float* in, float* out, int64_t rows, int V, hipStream_t st) {
+    if (rows <= 0) return;
+    if (V <= 1024) softmax_rows_inst<1>(in, out, rows, V, st);
+    else if (V <= 2048) softmax_rows_inst<2>(in, out, rows, V, st);
+    else if (V <= 4096) softmax_rows_inst<4>(in, out, rows, V, st);
+    else if (V <= 8192) softmax_rows_inst<8>(in, out, rows, V, st);
+    else if (V <= 16384) softmax_rows_inst<16>(in, out, rows, V, st);
+    else softmax_rows_inst<0>(in, out, rows, V, st);
+}
+
+void launch_copy_rows(const float* in, float* out, int64_t n_floats, hipStream_t st) {
+    if (n_floats <= 0 || in == out) return;
+    const int64_t n4 = n_floats >> 2;
+    const unsigned blocks = (unsigned)((n4 + TPB - 1) / TPB < 65536 ? (n4 + TPB - 1) / TPB : 65536);
+    hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(TPB), 0, st, reinterpret_cast<const float4*>(in),
+                       reinterpret_cast<float4*>(out), n4);
+}
+
+void launch_upsample_tokens(const int32_t* draft_tokens, int32_t* tokens_hi, int32_t* q_row, int B,
+                            int h, int w, int r, hipStream_t st) {
+    const int64_t n = (int64_t)B * h * r * w * r;
+    hipLaunchKernelGGL(k_upsample_tokens, dim3((unsigned)((n + TPB - 1) / TPB)), dim3(TPB), 0, st,
+                       draft_tokens, tokens_hi, q_row, B, h, w, r);
+}
+
+void launch_gather_rows(const float* q_lo, const int32_t* q_row, float* q_hi, int B, int n_lo,
+                        int n_hi, int V, hipStream_t st) {
+    hipLaunchKernelGGL(k_gather_rows, dim3(n_hi, B), dim3(TPB), 0, st, q_lo, q_row, q_hi, n_lo, n_hi, V);
+}
+
+void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t* inputs, int B,
+                         int L, hipStream_t st) {
+    const int64_t n = (int64_t)B * L;
+    hipLaunchKernelGGL(k_shift_inputs, dim3((unsigned)((n + TPB - 1) / TPB)), dim3(TPB), 0, st, prev,
+                       tokens_hi, inputs, B, L);
+}
+
+void launch_accept(const DecideArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(k_decide_init, dim3((4 * a.B + 255) / 256), dim3(256), 0, st, a.t0, a.stats, a.B,
+                       a.L);
+    if (a.V <= 1024) accept_inst<1>(a, st);
+    else if (a.V <= 2048) accept_inst<2>(a, st);
+    else if (a.V <= 4096) accept_inst<4>(a, st);
+    else if (a.V <= 8192) accept_inst<8>(a, st);
+    else if (a.V <= 16384) accept_inst<16>(a, st);
+    else accept_inst<0>(a, st);
+}
+
+void launch_mask_sample(const DecideArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(k_mask_sample, dim3((unsigned)(a.B * a.L)), dim3(TPB), 0, st, a);
+}
+
+}  // namespace mulo

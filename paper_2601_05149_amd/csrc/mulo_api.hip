@@ -1,0 +1,382 @@
+// C ABI of libmulo (see include/mulo.h): argument validation, the context with
+// its workspace, and the order in which the kernels of a verification step are
+// enqueued (Alg. 1 Steps 2-5 + residual re-draw).  Nothing here computes.
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/mulo.h"
+#include "mulo_internal.h"
+
+using namespace mulo;
+
+struct mulo_ctx {
+    mulo_model_cfg cfg;
+    mulo_weights w;
+    hipStream_t st;
+    int64_t maxM;
+    size_t esz;  // bytes per element of the model dtype
+    // workspace
+    float* x;        // [maxM, d] residual stream
+    void* xh;        // [maxM, d] normalised activations
+    void* qbuf;      // [maxB, nh, maxL, dh]
+    void* att;       // [maxM, d]
+    void* hmid;      // [maxM, f]
+    float* tmp;      // float32 path only: [maxM, max(3d, 2f)]
+    float* logits;   // [maxM, V]   (mulo_verify_step)
+    float* q_lo;     // [maxM, V]
+    float* rowmax;   // [maxM]
+    float* rowinv;   // [maxM]
+    int32_t* inputs;     // [maxM]
+    int32_t* tokens_hi;  // [maxM]
+    int32_t* q_row;      // [maxL]
+    void* base;      // single allocation
+    // optional per-launch timing (mulo_profile)
+    bool prof_on = false;
+    int prof_n = 0;
+    std::vector<hipEvent_t> prof_ev;   // 2 events per recorded launch
+    std::vector<int> prof_cls;
+};
+
+namespace {
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t off[13];
+    size_t total;
+};
+
+Layout plan(const mulo_model_cfg& c) {
+    const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
+    const size_t e = c.dtype == MULO_BF16 ? 2 : 4;
+    const size_t tmpw = c.dtype == MULO_F32 ? (3 * d > 2 * f ? 3 * d : 2 * f) : 0;
+    const size_t sizes[13] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
+                              M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4};
+    Layout l{};
+    size_t o = 0;
+    for (int i = 0; i < 13; ++i) {
+        l.off[i] = o;
+        o += align_up(sizes[i]);
+    }
+    l.total = o;
+    return l;
+}
+
+bool hip_ok(hipError_t e) { return e == hipSuccess; }
+
+constexpr int PROF_MAX = 16384;
+
+// Brackets the launches issued while it is alive with two events on the stream.
+struct ProfScope {
+    mulo_ctx* c;
+    int i;
+    ProfScope(mulo_ctx* ctx, int cls) : c(ctx), i(-1) {
+        if (!c->prof_on || c->prof_n >= PROF_MAX) return;
+        i = c->prof_n++;
+        c->prof_cls[i] = cls;
+        (void)hipEventRecord(c->prof_ev[2 * i], c->st);
+    }
+    ~ProfScope() {
+        if (i >= 0) (void)hipEventRecord(c->prof_ev[2 * i + 1], c->st);
+    }
+};
+#define PROF(cls) ProfScope prof_scope_##__LINE__(c, cls)
+
+mulo_status check_launch() { return hip_ok(hipGetLastError()) ? MULO_OK : MULO_ERR_HIP; }
+
+mulo_status check_forward_args(const mulo_ctx* ctx, const mulo_kv* kv, int B, int L, int P) {
+    if (!ctx || !kv || !kv->k || !kv->v) return MULO_ERR_NULL;
+    if (B < 1 || L < 1 || P < 0) return MULO_ERR_RANGE;
+    if (B > ctx->cfg.max_batch || L > ctx->cfg.max_block || (int64_t)P + L > ctx->cfg.max_seq)
+        return MULO_ERR_SHAPE;
+    return MULO_OK;
+}
+
+void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_t* tok, const void* emb,
+                     float* logits) {
+    const mulo_model_cfg& m = c->cfg;
+    const int M = B * L, d = m.d_model, f = m.d_ffn, V = m.vocab, dt = m.dtype;
+    const size_t e = c->esz;
+    hipStream_t st = c->st;
+    { PROF(MULO_PROF_NORM_EMBED); launch_embed(c->w.embed, dt, tok, emb, c->x, M, d, V, st); }
+    for (int l = 0; l < m.n_layers; ++l) {
+        RopeArgs ra{c->w.rope_cos, c->w.rope_sin, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l};
+        const char* wq = (const char*)c->w.wq + (size_t)l * d * d * e;
+        const char* wk = (const char*)c->w.wk + (size_t)l * d * d * e;
+        const char* wv = (const char*)c->w.wv + (size_t)l * d * d * e;
+        const char* wo = (const char*)c->w.wo + (size_t)l * d * d * e;
+        const char* wg = (const char*)c->w.w_gate + (size_t)l * f * d * e;
+        const char* wu = (const char*)c->w.w_up + (size_t)l * f * d * e;
+        const char* wd = (const char*)c->w.w_down + (size_t)l * d * f * e;
+        const char* g_attn = (const char*)c->w.attn_norm + (size_t)l * d * e;
+        const char* g_ffn = (const char*)c->w.ffn_norm + (size_t)l * d * e;
+        { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_attn, dt, c->xh, M, d, m.rms_eps, st); }
+        if (dt == MULO_BF16) {
+            { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
+            { PROF(MULO_PROF_ATTENTION);
+              launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, B, L, P, m.n_heads, m.head_dim, m.max_seq,
+                                    m.max_batch, l, st); }
+            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }
+            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
+            { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, st); }
+            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, st); }
+        } else {
+            const float* xh = (const float*)c->xh;
+            { PROF(MULO_PROF_GEMM_QKV);
+              launch_gemm_f32(xh, (const float*)wq, c->tmp, M, d, d, 3 * d, 0, st);
+              launch_gemm_f32(xh, (const float*)wk, c->tmp + d, M, d, d, 3 * d, 0, st);
+              launch_gemm_f32(xh, (const float*)wv, c->tmp + 2 * d, M, d, d, 3 * d, 0, st); }
+            { PROF(MULO_PROF_OTHER);
+              launch_rope_append_f32(c->tmp, (float*)c->qbuf, (float*)kv->k, (float*)kv->v, M, d, ra, st); }
+            { PROF(MULO_PROF_ATTENTION);
+              launch_attention_f32((const float*)c->qbuf, (const float*)kv->k, (const float*)kv->v, (float*)c->att,
+                                   nullptr, B, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st); }
+            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_f32((const float*)c->att, (const float*)wo, c->x, M, d, d, d, 1, st); }
+            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
+            { PROF(MULO_PROF_GEMM_GATE_UP);
+              launch_gemm_f32(xh, (const float*)wg, c->tmp, M, f, d, 2 * f, 0, st);
+              launch_gemm_f32(xh, (const float*)wu, c->tmp + f, M, f, d, 2 * f, 0, st); }
+            { PROF(MULO_PROF_OTHER); launch_swiglu_f32(c->tmp, (float*)c->hmid, M, f, st); }
+            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_f32((const float*)c->hmid, (const float*)wd, c->x, M, d, f, d, 1, st); }
+        }
+    }
+    { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, st); }
+    PROF(MULO_PROF_GEMM_LM_HEAD);
+    if (dt == MULO_BF16) launch_gemm_logits_bf16(c->xh, c->w.lm_head, logits, M, V, d, st);
+    else launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);
+}
+
+void enqueue_upsample(mulo_ctx* c, int B, int h, int w, int r, const float* draft, int input_is_probs,
+                      const int32_t* draft_tokens, int32_t* tokens_hi, float* q_lo, int32_t* q_row, float* q_hi) {
+    PROF(MULO_PROF_UPSAMPLE);
+    const int V = c->cfg.vocab;
+    const int64_t rows = (int64_t)B * h * w;
+    if (input_is_probs) launch_copy_rows(draft, q_lo, rows * V, c->st);
+    else launch_softmax_rows(draft, q_lo, rows, V, c->st);
+    launch_upsample_tokens(draft_tokens, tokens_hi, q_row, B, h, w, r, c->st);
+    if (q_hi) launch_gather_rows(q_lo, q_row, q_hi, B, h * w, h * r * w * r, V, c->st);
+}
+
+void enqueue_decide(mulo_ctx* c, const DecideArgs& a) {
+    { PROF(MULO_PROF_ACCEPT); launch_accept(a, c->st); }
+    { PROF(MULO_PROF_MASK_SAMPLE); launch_mask_sample(a, c->st); }
+}
+
+void fill_decide(DecideArgs& a, const mulo_ctx* ctx, int B, const mulo_step_params* p) {
+    a.B = B; a.L = p->L; a.V = ctx->cfg.vocab;
+    a.H = p->H; a.W = p->W; a.n0 = p->n0;
+    a.rho = p->radius < 0 ? -1 : p->radius * p->expand;
+    a.pool_k = p->pool_k < 1 ? 1 : p->pool_k;
+    a.nbr = p->nbr;
+    a.resample_mode = p->resample_mode;
+    a.key0 = (uint32_t)(p->seed & 0xFFFFFFFFu);
+    a.key1 = (uint32_t)(p->seed >> 32);
+    a.ctr_lo = (uint32_t)(p->rng_counter & 0xFFFFFFFFu);
+    a.ctr_hi24 = (uint32_t)((p->rng_counter >> 32) & 0xFFFFFFu);
+    a.rowmax = ctx->rowmax;
+    a.rowinv = ctx->rowinv;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mulo_status_string(mulo_status s) {
+    switch (s) {
+        case MULO_OK: return "ok";
+        case MULO_ERR_NULL: return "a required pointer is NULL";
+        case MULO_ERR_SHAPE: return "inconsistent sizes";
+        case MULO_ERR_RANGE: return "argument out of range";
+        case MULO_ERR_ALLOC: return "device allocation failed";
+        case MULO_ERR_HIP: return "HIP call or kernel launch failed";
+        case MULO_ERR_UNSUPPORTED: return "configuration not supported by these kernels";
+    }
+    return "unknown status";
+}
+
+mulo_status mulo_check_model_cfg(const mulo_model_cfg* c) {
+    if (!c) return MULO_ERR_NULL;
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->head_dim < 2 || c->d_ffn < 1 ||
+        c->vocab < 4 || c->max_batch < 1 || c->max_seq < 1 || c->max_block < 1 || !(c->rms_eps >= 0.f))
+        return MULO_ERR_RANGE;
+    if (c->dtype != MULO_F32 && c->dtype != MULO_BF16) return MULO_ERR_RANGE;
+    if ((int64_t)c->n_heads * c->head_dim != c->d_model || (c->head_dim & 1)) return MULO_ERR_SHAPE;
+    if (c->max_block > c->max_seq) return MULO_ERR_SHAPE;
+    if ((c->vocab & 3) || c->vocab > 262144) return MULO_ERR_UNSUPPORTED;
+    if ((int64_t)c->max_batch * c->max_block > (1 << 22)) return MULO_ERR_UNSUPPORTED;
+    if (c->dtype == MULO_BF16) {
+        if (c->head_dim != 64 && c->head_dim != 128) return MULO_ERR_UNSUPPORTED;
+        if ((c->d_model % 128) || (c->d_ffn % 64) || (c->max_seq % 8) || (c->max_block % 4))
+            return MULO_ERR_UNSUPPORTED;
+    } else {
+        if (c->max_seq + c->head_dim > 15000) return MULO_ERR_UNSUPPORTED;  // scores of a row live in LDS
+    }
+    return MULO_OK;
+}
+
+mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mulo_step_params* p) {
+    if (!c || !p) return MULO_ERR_NULL;
+    if (B < 1 || p->H < 1 || p->W < 1 || p->L < 1 || p->n0 < 0 || p->radius < -1 || p->expand < 0 ||
+        p->pool_k < 1 || p->resample_mode < 0 || p->resample_mode > 1)
+        return MULO_ERR_RANGE;
+    if ((int64_t)p->radius * p->expand > 4096) return MULO_ERR_RANGE;
+    if (B > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
+    if (p->L % p->W || p->n0 % p->W || (int64_t)p->n0 + p->L > (int64_t)p->H * p->W) return MULO_ERR_SHAPE;
+    if (p->pool_k > 1 && !p->nbr) return MULO_ERR_NULL;
+    if (p->pool_k > c->vocab) return MULO_ERR_RANGE;
+    return MULO_OK;
+}
+
+uint64_t mulo_workspace_bytes(const mulo_model_cfg* cfg) {
+    if (mulo_check_model_cfg(cfg) != MULO_OK) return 0;
+    return plan(*cfg).total;
+}
+
+mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* hip_stream, mulo_ctx** out) {
+    if (!cfg || !w || !out) return MULO_ERR_NULL;
+    const mulo_status s = mulo_check_model_cfg(cfg);
+    if (s != MULO_OK) return s;
+    if (!w->embed || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm || !w->w_gate ||
+        !w->w_up || !w->w_down || !w->final_norm || !w->lm_head || !w->rope_cos || !w->rope_sin)
+        return MULO_ERR_NULL;
+    int ndev = 0;
+    if (!hip_ok(hipGetDeviceCount(&ndev)) || ndev < 1) return MULO_ERR_HIP;
+    mulo_ctx* c = new (std::nothrow) mulo_ctx();
+    if (!c) return MULO_ERR_ALLOC;
+    c->cfg = *cfg;
+    c->w = *w;
+    c->st = (hipStream_t)hip_stream;
+    c->maxM = (int64_t)cfg->max_batch * cfg->max_block;
+    c->esz = cfg->dtype == MULO_BF16 ? 2 : 4;
+    const Layout l = plan(*cfg);
+    if (!hip_ok(hipMalloc(&c->base, l.total))) {
+        (void)hipGetLastError();
+        delete c;
+        return MULO_ERR_ALLOC;
+    }
+    char* b = (char*)c->base;
+    c->x = (float*)(b + l.off[0]);
+    c->xh = b + l.off[1];
+    c->qbuf = b + l.off[2];
+    c->att = b + l.off[3];
+    c->hmid = b + l.off[4];
+    c->tmp = (float*)(b + l.off[5]);
+    c->logits = (float*)(b + l.off[6]);
+    c->q_lo = (float*)(b + l.off[7]);
+    c->rowmax = (float*)(b + l.off[8]);
+    c->rowinv = (float*)(b + l.off[9]);
+    c->inputs = (int32_t*)(b + l.off[10]);
+    c->tokens_hi = (int32_t*)(b + l.off[11]);
+    c->q_row = (int32_t*)(b + l.off[12]);
+    *out = c;
+    return MULO_OK;
+}
+
+void mulo_destroy(mulo_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->st);
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    (void)hipFree(ctx->base);
+    delete ctx;
+}
+
+mulo_status mulo_profile(mulo_ctx* ctx, int32_t enable) {
+    if (!ctx) return MULO_ERR_NULL;
+    if (enable && ctx->prof_ev.empty()) {
+        ctx->prof_ev.resize(2 * PROF_MAX);
+        ctx->prof_cls.resize(PROF_MAX);
+        for (auto& e : ctx->prof_ev)
+            if (!hip_ok(hipEventCreate(&e))) return MULO_ERR_HIP;
+    }
+    ctx->prof_on = enable != 0;
+    return MULO_OK;
+}
+
+mulo_status mulo_profile_read(mulo_ctx* ctx, float* ms, int32_t* launches) {
+    if (!ctx || !ms || !launches) return MULO_ERR_NULL;
+    for (int i = 0; i < MULO_PROF_N; ++i) { ms[i] = 0.f; launches[i] = 0; }
+    if (!hip_ok(hipStreamSynchronize(ctx->st))) return MULO_ERR_HIP;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        float t = 0.f;
+        if (!hip_ok(hipEventElapsedTime(&t, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]))) return MULO_ERR_HIP;
+        ms[ctx->prof_cls[i]] += t;
+        launches[ctx->prof_cls[i]] += 1;
+    }
+    ctx->prof_n = 0;
+    return MULO_OK;
+}
+
+mulo_status mulo_upsample_draft(mulo_ctx* ctx, int32_t B, int32_t h, int32_t w, int32_t r, const float* draft,
+                                int32_t input_is_probs, const int32_t* draft_tokens, int32_t* tokens_hi,
+                                float* q_lo, int32_t* q_row, float* q_hi) {
+    if (!ctx || !draft || !draft_tokens || !tokens_hi || !q_lo || !q_row) return MULO_ERR_NULL;
+    if (B < 1 || h < 1 || w < 1 || r < 1) return MULO_ERR_RANGE;
+    if ((int64_t)B * h * r * w * r > ((int64_t)1 << 30)) return MULO_ERR_RANGE;
+    enqueue_upsample(ctx, B, h, w, r, draft, input_is_probs, draft_tokens, tokens_hi, q_lo, q_row, q_hi);
+    return check_launch();
+}
+
+mulo_status mulo_verify_forward(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t L, int32_t P,
+                                const int32_t* in_tokens, const void* in_embeds, float* logits) {
+    const mulo_status s = check_forward_args(ctx, kv, B, L, P);
+    if (s != MULO_OK) return s;
+    if ((!in_tokens && !in_embeds) || !logits) return MULO_ERR_NULL;
+    enqueue_forward(ctx, kv, B, L, P, in_tokens, in_embeds, logits);
+    return check_launch();
+}
+
+mulo_status mulo_accept_local_resample(mulo_ctx* ctx, int32_t B, const mulo_step_params* p, const float* logits,
+                                       const float* q, const int32_t* q_row, int64_t q_batch_stride,
+                                       const int32_t* draft_tokens, int32_t* tokens_out, uint8_t* accept,
+                                       uint8_t* mask, int32_t* t0, int32_t* stats, float* p_probs) {
+    if (!ctx || !p || !logits || !q || !draft_tokens || !tokens_out || !accept || !mask || !t0 || !stats)
+        return MULO_ERR_NULL;
+    const mulo_status s = mulo_check_step_params(&ctx->cfg, B, p);
+    if (s != MULO_OK) return s;
+    if (q_batch_stride < 0) return MULO_ERR_RANGE;
+    DecideArgs a{};
+    fill_decide(a, ctx, B, p);
+    a.logits = logits; a.q = q; a.q_row = q_row; a.q_batch_stride = q_batch_stride;
+    a.draft_tokens = draft_tokens; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
+    a.t0 = t0; a.stats = stats; a.p_probs = p_probs;
+    enqueue_decide(ctx, a);
+    return check_launch();
+}
+
+mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, const mulo_step_params* p,
+                             int32_t h_blk, int32_t w, int32_t r, const float* draft, int32_t input_is_probs,
+                             const int32_t* draft_tokens, const int32_t* prev_tokens, int32_t* tokens_out,
+                             uint8_t* accept, uint8_t* mask, int32_t* t0, int32_t* stats, int32_t* tokens_hi,
+                             float* logits) {
+    if (!ctx || !p || !draft || !draft_tokens || !prev_tokens || !tokens_out || !accept || !mask || !t0 ||
+        !stats)
+        return MULO_ERR_NULL;
+    mulo_status s = mulo_check_step_params(&ctx->cfg, B, p);
+    if (s != MULO_OK) return s;
+    if (h_blk < 1 || w < 1 || r < 1) return MULO_ERR_RANGE;
+    if ((int64_t)h_blk * r * w * r != p->L || w * r != p->W) return MULO_ERR_SHAPE;
+    s = check_forward_args(ctx, kv, B, p->L, P);
+    if (s != MULO_OK) return s;
+
+    const int L = p->L, V = ctx->cfg.vocab, n_lo = h_blk * w;
+    hipStream_t st = ctx->st;
+    int32_t* thi = tokens_hi ? tokens_hi : ctx->tokens_hi;
+    float* lg = logits ? logits : ctx->logits;
+    // Step 2
+    enqueue_upsample(ctx, B, h_blk, w, r, draft, input_is_probs, draft_tokens, thi, ctx->q_lo, ctx->q_row, nullptr);
+    // Step 3: inputs [prev, x~_0 .. x~_{L-2}] so that logit row j is p of draft position j
+    { mulo_ctx* c = ctx; PROF(MULO_PROF_UPSAMPLE); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st); }
+    enqueue_forward(ctx, kv, B, L, P, ctx->inputs, nullptr, lg);
+    // Steps 4-5 + residual re-draw
+    DecideArgs a{};
+    fill_decide(a, ctx, B, p);
+    a.logits = lg; a.q = ctx->q_lo; a.q_row = ctx->q_row; a.q_batch_stride = (int64_t)n_lo * V;
+    a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
+    a.t0 = t0; a.stats = stats; a.p_probs = nullptr;
+    enqueue_decide(ctx, a);
+    return check_launch();
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal launcher declarations shared by the translation units of libmulo.
+// Every launcher only enqueues work on `st`; shapes are validated by the caller
+// (mulo_api.hip) before any of them runs.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mulo {
+
+// ---- decision stage (decide.hip) -------------------------------------------
+struct DecideArgs {
+    int B, L, V;
+    int H, W, n0;
+    int rho;          // Chebyshev radius expand*radius; -1 = raster-scan rule
+    int pool_k;
+    const int32_t* nbr;
+    int resample_mode;
+    uint32_t key0, key1, ctr_lo, ctr_hi24;
+    const float* logits;        // [B, L, V]
+    const float* q;             // rows of V floats
+    const int32_t* q_row;       // [L] or nullptr
+    int64_t q_batch_stride;
+    const int32_t* draft_tokens;  // [B, L]
+    int32_t* tokens_out;
+    uint8_t* accept;
+    uint8_t* mask;
+    int32_t* t0;      // [B]
+    int32_t* stats;   // [B, 4]
+    float* p_probs;   // [B, L, V] or nullptr
+    float* rowmax;    // [B*L] workspace
+    float* rowinv;    // [B*L] workspace: 1 / sum exp
+};
+void launch_softmax_rows(const float* in, float* out, int64_t rows, int V, hipStream_t st);
+void launch_copy_rows(const float* in, float* out, int64_t n_floats, hipStream_t st);
+void launch_upsample_tokens(const int32_t* draft_tokens, int32_t* tokens_hi, int32_t* q_row, int B,
+                            int h, int w, int r, hipStream_t st);
+void launch_gather_rows(const float* q_lo, const int32_t* q_row, float* q_hi, int B, int n_lo,
+                        int n_hi, int V, hipStream_t st);
+void launch_accept(const DecideArgs& a, hipStream_t st);       // init + softmax statistics + accept test
+void launch_mask_sample(const DecideArgs& a, hipStream_t st);  // Eq. 6-7 mask + residual draw
+void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t* inputs, int B,
+                         int L, hipStream_t st);
+
+// ---- decoder forward (elementwise.hip, gemm.hip, attention.hip) ------------
+struct RopeArgs {
+    const float* cos;   // [max_seq, dh/2]
+    const float* sin;
+    int L, P, n_heads, head_dim, max_seq, max_batch, layer;
+};
+// x[m, :] = embed[clamp(tok[m])]  (float32 residual stream); T = float or bf16 storage
+void launch_embed(const void* embed, int dtype, const int32_t* tok, const void* in_embeds, float* x,
+                  int M, int d, int V, hipStream_t st);
+void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps,
+                    hipStream_t st);
+
+// bf16 MFMA GEMMs, C = A[M,K] * W[N,K]^T with fused epilogues
+void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
+                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra,
+                          hipStream_t st);
+void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K,
+                            hipStream_t st);
+void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f,
+                             int d, hipStream_t st);
+void launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, int M, int V, int d,
+                             hipStream_t st);
+void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
+                           int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,
+                           int layer, hipStream_t st);
+
+// float32 path (small configurations): plain tiled GEMM + separate elementwise kernels
+void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc,
+                     int accumulate, hipStream_t st);
+void launch_rope_append_f32(const float* qkv, float* q_out, float* k_cache, float* v_cache, int M,
+                            int d, const RopeArgs& ra, hipStream_t st);
+void launch_swiglu_f32(const float* gu, float* h, int M, int f, hipStream_t st);
+void launch_attention_f32(const float* q, const float* k_cache, const float* v_cache, float* out,
+                          float* scratch, int B, int L, int P, int n_heads, int head_dim,
+                          int max_seq, int max_batch, int layer, hipStream_t st);
+
+}  // namespace mulo

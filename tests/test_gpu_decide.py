@@ -1,0 +1,218 @@
+"""GPU parity of the decision stage (up-sampling, accept test, local expansion,
+residual re-draw) against the CPU oracle, through the C ABI.
+
+Tolerances: token / mask / index outputs bit-exact; accept flags may differ only
+at near ties |pbar - u q| < 1e-4 q (count reported); re-drawn tokens may differ
+only when the integer threshold lies within 2^-20 of a CDF boundary;
+probabilities within 1e-5 absolute."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_05149_amd as mulo
+from oracle import step as ST
+from oracle import upsample as UP
+from tests.gpu_util import DEV, compare_decisions, decide_buffers, dev, make_ctx, say, to_np
+from workloads import generators as G
+
+pytestmark = pytest.mark.gpu
+
+_CTX = {}
+
+
+def decide_ctx(V, max_batch, max_block):
+    """A context whose decoder is a stub (the decision entry points only need
+    the vocabulary, the stream and the row-statistics workspace)."""
+    key = (V, max_batch, max_block)
+    if key not in _CTX:
+        m = dict(n_layers=1, d_model=64, n_heads=1, head_dim=64, d_ffn=64, vocab=V, dtype="f32", rms_eps=1e-5)
+        w = G.make_weights(m, seed=0, threads=4)
+        _CTX[key] = make_ctx(m, w, max_batch, max_block + 8, max_block)[0]
+    return _CTX[key]
+
+
+def clean_inputs(B, L, V, sigma, seed):
+    """Target logits N(0, 1.28) i.i.d., draft logits = target + sigma * noise,
+    draft tokens drawn from softmax(draft logits)."""
+    zp = G.normal_logits((B, L, V), 1.28, seed, tag=10)
+    zq = zp + sigma * G.normal_logits((B, L, V), 1.0, seed, tag=11)
+    q = UP.softmax_rows(zq).astype(np.float32)
+    toks = G.sample_categorical(zq, seed, tag=12)
+    return zp, q, toks
+
+
+def run_decide(ctx, zp, q, toks, q_row=None, p_probs=False, **pk):
+    B, L, V = zp.shape
+    nbr = pk.pop("nbr", None)
+    nbr_d = dev(nbr) if nbr is not None else None
+    params = mulo.make_params(nbr=nbr_d, pool_k=1 if nbr is None else nbr.shape[1], **pk)
+    out = decide_buffers(B, L)
+    pp = torch.empty(B, L, V, device=DEV) if p_probs else None
+    mulo.mulo_accept_local_resample(ctx, B, params, dev(zp, torch.float32), dev(q, torch.float32),
+                                    None if q_row is None else dev(q_row, torch.int32),
+                                    q.shape[1] * V, dev(toks, torch.int32), out["tokens_out"],
+                                    out["accept"], out["mask"], out["t0"], out["stats"], pp)
+    torch.cuda.synchronize()
+    res = to_np(out)
+    if pp is not None:
+        res["p"] = pp.cpu().numpy()
+    return res
+
+
+# ------------------------------------------------------------------ Step 2
+@pytest.mark.parametrize("B,h,w,r,V", [(1, 8, 8, 2, 1024), (2, 5, 7, 2, 1000), (1, 4, 4, 4, 16384),
+                                        (2, 3, 3, 1, 2048), (1, 2, 3, 2, 20000), (3, 6, 2, 3, 8192)])
+def test_upsample_parity(B, h, w, r, V):
+    say("upsample B=%d h=%d w=%d r=%d V=%d" % (B, h, w, r, V))
+    ctx = decide_ctx(V, 4, 64)
+    dl = G.normal_logits((B, h * w, V), 2.0, seed=1, tag=V)
+    dt = G.uniform_tokens((B, h * w), V, seed=1, tag=V)
+    x_hi, q_lo, q_row, q_hi = UP.upsample_draft(dl, dt, h, w, r, materialise=True)
+    T = h * r * w * r
+    g = dict(tokens_hi=torch.empty(B, T, dtype=torch.int32, device=DEV), q_lo=torch.empty(B, h * w, V, device=DEV),
+             q_row=torch.empty(T, dtype=torch.int32, device=DEV), q_hi=torch.empty(B, T, V, device=DEV))
+    mulo.mulo_upsample_draft(ctx, B, h, w, r, torch.tensor(dl, device=DEV), 0, torch.tensor(dt, device=DEV),
+                             g["tokens_hi"], g["q_lo"], g["q_row"], g["q_hi"])
+    torch.cuda.synchronize()
+    g = to_np(g)
+    assert np.array_equal(g["tokens_hi"], x_hi) and np.array_equal(g["q_row"], q_row)
+    err = np.abs(g["q_lo"] - q_lo).max()
+    say("  max |q_lo - oracle| = %.3g" % err)
+    assert err <= 1e-5
+    assert np.abs(g["q_lo"].astype(np.float64).sum(-1) - 1).max() < 1e-5
+    assert np.array_equal(g["q_hi"], g["q_lo"][:, q_row])           # children carry the parent's row, bit for bit
+    # probabilities as input are copied unchanged
+    g2 = torch.empty(B, h * w, V, device=DEV)
+    mulo.mulo_upsample_draft(ctx, B, h, w, r, torch.tensor(q_lo, device=DEV), 1, torch.tensor(dt, device=DEV),
+                             torch.empty(B, T, dtype=torch.int32, device=DEV), g2,
+                             torch.empty(T, dtype=torch.int32, device=DEV), None)
+    assert np.array_equal(g2.cpu().numpy(), q_lo)
+
+
+# --------------------------------------------------------------- Steps 4-5 + re-draw
+CASES = [
+    # B, H, W, n0, L, V, sigma, radius, expand, mode, pool_k
+    (1, 16, 16, 0, 256, 1024, 1.0, 1, 1, 0, 1),
+    (4, 32, 32, 512, 256, 8192, 1.0, 1, 2, 0, 1),
+    (1, 48, 48, 1728, 576, 16384, 1.0, 1, 1, 0, 1),
+    (2, 10, 10, 20, 60, 1000, 0.5, 2, 1, 0, 8),        # ragged vocabulary, pooled numerator (Eq. 3)
+    (2, 16, 16, 64, 128, 4096, 2.0, 1, 1, 1, 1),       # expanded positions drawn from p
+    (2, 16, 16, 0, 256, 2048, 0.5, -1, 1, 0, 1),       # raster-scan rule
+    (2, 16, 16, 0, 256, 2048, 1.0, 0, 1, 0, 1),        # radius 0: only the rejected positions
+    (1, 8, 8, 0, 64, 20000, 1.0, 3, 1, 0, 1),          # vocabulary beyond the register-resident path
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "B%d_%dx%d_n%d_L%d_V%d_s%g_r%d_e%d_m%d_k%d" % c)
+def test_decide_parity(case):
+    B, H, W, n0, L, V, sigma, radius, expand, mode, k = case
+    say("decide case %r" % (case,))
+    ctx = decide_ctx(V, 4, 1024)
+    zp, q, toks = clean_inputs(B, L, V, sigma, seed=3)
+    nbr = G.neighbour_table(V, k, seed=3) if k > 1 else None
+    kw = dict(W=W, n0=n0, radius=radius, expand=expand, seed=77, rng_counter=(5 << 32) | 9)
+    ref = ST.decide(zp, q, None, toks, nbr=nbr, mode=mode, **kw)
+    got = run_decide(ctx, zp, q, toks, p_probs=True, H=H, L=L, nbr=nbr, resample_mode=mode, **kw)
+    perr = np.abs(got["p"] - ref["p"]).max()
+    rep = compare_decisions(got, ref, toks, q, None, mode=mode, label=str(case))
+    say("  acc rate %.3f marked %.3f | max|p err| %.3g | %r" % (ref["accept"].mean(), ref["mask"].mean(), perr, rep))
+    assert perr <= 1e-5
+    assert rep["sequences_checked"] >= 1
+    # run-to-run determinism
+    again = run_decide(ctx, zp, q, toks, H=H, L=L, nbr=nbr, resample_mode=mode, **kw)
+    for name in ("tokens_out", "accept", "mask", "t0", "stats"):
+        assert np.array_equal(again[name], got[name])
+
+
+def test_q_row_indirection_matches_materialised_rows():
+    # q given as low-res rows + q_row (what the step uses) == q given per position
+    B, h, w, r, V = 2, 4, 8, 2, 4096
+    H, W, L = 8, 16, 128
+    ctx = decide_ctx(V, 4, 1024)
+    dl = G.normal_logits((B, h * w, V), 2.0, seed=4)
+    dt = G.sample_categorical(dl, seed=4)
+    x_hi, q_lo, q_row, q_hi = UP.upsample_draft(dl, dt, h, w, r, materialise=True)
+    zp = q_hi * 0 + np.log(np.maximum(q_hi, 1e-30)) + G.normal_logits((B, L, V), 1.0, seed=4, tag=1)
+    kw = dict(W=W, n0=0, radius=1, expand=1, seed=1, rng_counter=2)
+    ref = ST.decide(zp, q_lo, q_row, x_hi, **kw)
+    a = run_decide(ctx, zp.astype(np.float32), q_lo, x_hi, q_row=q_row, H=H, L=L, **kw)
+    b = run_decide(ctx, zp.astype(np.float32), q_hi, x_hi, H=H, L=L, **kw)
+    for name in ("tokens_out", "accept", "mask", "t0", "stats"):
+        assert np.array_equal(a[name], b[name])
+    rep = compare_decisions(a, ref, x_hi, q_lo, q_row, label="q_row")
+    say("  q_row case: acc %.3f %r" % (ref["accept"].mean(), rep))
+
+
+def test_q_equal_p_accepts_everything_on_device():
+    B, L, V = 2, 128, 8192
+    ctx = decide_ctx(V, 4, 1024)
+    zp, _, toks = clean_inputs(B, L, V, 1.0, seed=5)
+    first = run_decide(ctx, zp, np.full((B, L, V), 1.0 / V, np.float32), toks, p_probs=True, H=8, W=16, n0=0, L=L,
+                       radius=1, seed=0, rng_counter=0)
+    got = run_decide(ctx, zp, first["p"], toks, H=8, W=16, n0=0, L=L, radius=1, seed=0, rng_counter=0)
+    assert got["accept"].all() and not got["mask"].any()
+    assert (got["t0"] == L).all() and np.array_equal(got["tokens_out"], toks)
+    assert np.array_equal(got["stats"][:, :3], [[L, 0, 0]] * B)
+
+
+def test_all_rejected_empty_residual_and_out_of_range_tokens():
+    B, L, V = 1, 32, 1024
+    ctx = decide_ctx(V, 4, 1024)
+    zp = G.normal_logits((B, L, V), 1.0, seed=6)
+    zp[:, :, :8] -= 60.0                              # target has (numerically) no mass on the first 8 entries
+    q = np.zeros((B, L, V), np.float32)
+    q[:, :, :8] = 0.125                               # draft has all of its mass there
+    toks = G.uniform_tokens((B, L), 8, seed=6)
+    kw = dict(W=8, n0=0, radius=1, expand=1, seed=3, rng_counter=1)
+    ref = ST.decide(zp, q, None, toks, **kw)
+    got = run_decide(ctx, zp, q, toks, H=4, L=L, **kw)
+    assert not ref["accept"].any() and ref["t0"][0] == 0 and ref["mask"].all()
+    rep = compare_decisions(got, ref, toks, q, None, label="all rejected")
+    assert rep["flips"] == 0
+    # q >= p everywhere (q need not be normalised for the test) and a position marked by a rejected
+    # neighbour: the residual max(0, p - q) is empty on both sides -> the draw falls back to p
+    p = ST.A.target_probs(zp)
+    q2 = (p * np.float32(1.001)).astype(np.float32)
+    q2[0, 5] = q[0, 5]                                # only position 5 is rejected
+    toks2 = toks.copy()
+    ref2 = ST.decide(zp, q2, None, toks2, **kw)
+    got2 = run_decide(ctx, zp, q2, toks2, H=4, L=L, **kw)
+    assert ref2["accept"].sum() >= L - 2 and not ref2["accept"][0, 5] and ref2["mask"].sum() > 1
+    compare_decisions(got2, ref2, toks2, q2, None, label="empty residual")
+    # ids outside the codebook are clamped, never dereferenced
+    bad = toks.copy()
+    bad[0, 3], bad[0, 4] = V + 5, -3
+    clamped = np.clip(bad, 0, V - 1)
+    ref3 = ST.decide(zp, q, None, clamped, **kw)
+    got3 = run_decide(ctx, zp, q, bad, H=4, L=L, **kw)
+    compare_decisions(got3, ref3, clamped, q, None, label="clamped ids")
+
+
+def test_argument_errors_are_reported_not_launched():
+    ctx = decide_ctx(1024, 4, 1024)
+    zp, q, toks = clean_inputs(1, 64, 1024, 1.0, seed=7)
+    with pytest.raises(mulo.MuloError) as e:
+        run_decide(ctx, zp, q, toks, H=8, W=7, n0=0, L=64, radius=1, seed=0, rng_counter=0)   # L not whole rows
+    assert e.value.status == 2
+    with pytest.raises(mulo.MuloError) as e:
+        run_decide(ctx, zp, q, toks, H=4, W=8, n0=0, L=64, radius=1, seed=0, rng_counter=0)   # block past the grid
+    assert e.value.status == 2
+    with pytest.raises(mulo.MuloError) as e:
+        run_decide(ctx, zp, q, toks, H=8, W=8, n0=0, L=64, radius=-3, seed=0, rng_counter=0)
+    assert e.value.status == 3
+
+
+@pytest.mark.parametrize("name,B,L,radius", [("cfg4", 4, 1024, 2), ("cfg5_L256", 16, 256, 1)])
+def test_decide_full_size(name, B, L, radius):
+    """Decision stage at the full shape of the 7B-class workloads (V = 16384,
+    64x64 grid, last block), in the launch configuration the benchmark times."""
+    V, H, W = 16384, 64, 64
+    say("full-size decide %s" % name)
+    ctx = decide_ctx(V, 16, 1024)
+    zp, q, toks = clean_inputs(B, L, V, 1.0, seed=8)
+    kw = dict(W=W, n0=H * W - L, radius=radius, expand=1, seed=0, rng_counter=3)
+    ref = ST.decide(zp, q, None, toks, **kw)
+    got = run_decide(ctx, zp, q, toks, H=H, L=L, **kw)
+    rep = compare_decisions(got, ref, toks, q, None, label=name)
+    say("  %s: acc %.3f marked %.3f %r" % (name, ref["accept"].mean(), ref["mask"].mean(), rep))
+    assert rep["sequences_checked"] >= B - 2

@@ -1,0 +1,86 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and its host-only argument checks behave.  No compute."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2601_05149_amd as mulo
+from paper_2601_05149_amd import binding as BD
+from workloads import configs as WC
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(BD.LIB_PATH):
+        from paper_2601_05149_amd import build
+        build.build_lib()
+    return mulo.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "mulo.h")).read()
+    declared = set(re.findall(r"MULO_API\s+[\w\s\*]+?\b(mulo_\w+)\s*\(", header))
+    assert declared == set(BD.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = {lib.mulo_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and all(seen)
+    assert lib.mulo_status_string(99)
+
+
+def test_model_cfg_checks(lib):
+    for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5_L1024"):
+        c = WC.get(name)
+        cfg = mulo.make_cfg(c["model"], c["B"], c["max_seq"], c["L"])
+        assert lib.mulo_check_model_cfg(C.byref(cfg)) == 0
+        assert lib.mulo_workspace_bytes(C.byref(cfg)) > 0
+    c = WC.get("cfg2")
+    bad = mulo.make_cfg(c["model"], 4, c["max_seq"], 256)
+    bad.n_heads = 15
+    assert lib.mulo_check_model_cfg(C.byref(bad)) == 2          # heads * head_dim != d
+    bad = mulo.make_cfg(c["model"], 4, c["max_seq"], 256)
+    bad.vocab = 8190
+    assert lib.mulo_check_model_cfg(C.byref(bad)) == 6
+    bad = mulo.make_cfg(c["model"], 0, c["max_seq"], 256)
+    assert lib.mulo_check_model_cfg(C.byref(bad)) == 3
+    bad = mulo.make_cfg(c["model"], 4, 100, 256)
+    assert lib.mulo_check_model_cfg(C.byref(bad)) == 2          # block longer than the cache
+    assert lib.mulo_check_model_cfg(None) == 1
+    assert lib.mulo_workspace_bytes(C.byref(bad)) == 0
+
+
+def test_step_param_checks(lib):
+    c = WC.get("cfg2")
+    cfg = mulo.make_cfg(c["model"], 4, c["max_seq"], 256)
+    ok = lambda **kw: lib.mulo_check_step_params(C.byref(cfg), kw.pop("B", 4), C.byref(BD.StepParams(**kw)))
+    base = dict(H=32, W=32, n0=256, L=256, radius=1, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0,
+                rng_counter=0)
+    assert ok(**base) == 0
+    assert ok(**{**base, "L": 250}) == 2            # not whole rows
+    assert ok(**{**base, "n0": 40}) == 2            # block does not start on a row
+    assert ok(**{**base, "n0": 896}) == 2           # runs past the grid
+    assert ok(**{**base, "L": 512}) == 2            # longer than max_block
+    assert ok(**{**base, "radius": -2}) == 3
+    assert ok(**{**base, "radius": -1}) == 0        # raster-scan rule
+    assert ok(**{**base, "pool_k": 4}) == 1         # pooling without a table
+    assert ok(**{**base, "resample_mode": 2}) == 3
+    assert ok(**{**base, "B": 5}) == 2
+    assert lib.mulo_check_step_params(C.byref(cfg), 4, None) == 1
+
+
+def test_create_rejects_bad_arguments_without_a_gpu_call(lib):
+    out = C.c_void_p()
+    c = WC.get("cfg1")
+    cfg = mulo.make_cfg(c["model"], 1, c["max_seq"], 256)
+    assert lib.mulo_create(None, None, None, C.byref(out)) == 1
+    w = BD.Weights()                                 # all NULL
+    assert lib.mulo_create(C.byref(cfg), C.byref(w), None, C.byref(out)) == 1
+    assert not out.value
+    lib.mulo_destroy(None)                           # allowed

@@ -216,6 +216,28 @@ def test_bf16_contract_keeps_logits_close_to_unrounded():
     assert torch.equal(o.k, o.k.to(torch.bfloat16).to(o.k.dtype))      # cache holds bf16 values
 
 
+def test_bf16_rounding_makes_the_forward_chaotic():
+    """Why whole-model bf16 parity cannot be held to a fixed small bound: with the
+    rounding contract on, a perturbation of the input far below float32 rounding
+    (1e-7 relative) moves the logits by the format's own noise, about 10^4 times
+    what the smooth (unrounded) model does, and the rounded and exact models are
+    already ~2e-2 apart at 8 layers of width 1024."""
+    from workloads import configs as C
+    m = C.model("small")
+    w = G.make_weights(m, seed=0)
+    cos, sin = G.rope_table(96, m["head_dim"])
+    toks = G.uniform_tokens((1, 96), m["vocab"], 0)
+    emb = w["embed"].double()[torch.as_tensor(toks).long()].numpy()
+    run = lambda rb, e: D.DecoderOracle(m, w, cos, sin, 1, 96, rb).forward(toks, 0, embeds=e).numpy()
+    zr, zu = run(True, emb), run(False, emb)
+    zr_p, zu_p = run(True, emb * (1 + 1e-7)), run(False, emb * (1 + 1e-7))
+    assert np.abs(zu_p - zu).max() < 1e-6                       # exact model: smooth
+    assert np.abs(zr_p - zr).max() > 2e-3                       # rounded model: amplified to the noise floor
+    assert 1e-2 < np.abs(zr - zu).max() < 5e-2                  # the floor itself at this depth
+    rms = lambda a: np.sqrt((a ** 2).mean())
+    assert rms(zr_p - zr) < 1.5 * rms(zr - zu)                  # and it saturates there
+
+
 # ------------------------------------------------------------- generators
 def test_generators_are_seeded_and_shaped():
     m = dict(n_layers=2, d_model=64, n_heads=4, head_dim=16, d_ffn=96, vocab=128, dtype="bf16")

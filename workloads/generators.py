@@ -81,10 +81,18 @@ def sample_categorical(logits, seed, tag=0):
     return np.argmax(logits + g, axis=-1).astype(np.int32)
 
 
-def random_kv(shape, seed, tag=0, dtype=torch.bfloat16, std=1.0):
+def random_kv(shape, seed, tag=0, dtype=torch.bfloat16, std=1.0, threads=None):
     """Direct fill of cache rows with N(0, std) values (timing and full-size
-    parity runs where a real prefill of thousands of rows is too slow on the CPU)."""
-    return torch.from_numpy(_normal(shape, std, seed, 5, tag)).to(dtype)
+    parity runs where a real prefill of thousands of rows is too slow on the CPU).
+    Generated slice by slice along the first axis (one generator per slice)."""
+    out = torch.empty(shape, dtype=dtype)
+
+    def run(i):
+        out[i].copy_(torch.from_numpy(_normal(tuple(shape[1:]), std, seed, 5, tag, i)))
+
+    with ThreadPoolExecutor(threads or min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(run, range(shape[0])))
+    return out
 
 
 def neighbour_table(V, k, seed, tag=0):
