@@ -213,10 +213,10 @@ enum {
     MULO_PROF_GEMM_LM_HEAD = 4,
     MULO_PROF_ATTENTION = 5,
     MULO_PROF_NORM_EMBED = 6, /* embedding lookup, RMSNorm */
-    MULO_PROF_UPSAMPLE = 7,   /* draft softmax, token replication, input shift */
+    MULO_PROF_UPSAMPLE = 7,   /* draft softmax (or copy) + token replication */
     MULO_PROF_ACCEPT = 8,     /* target softmax statistics + accept test */
     MULO_PROF_MASK_SAMPLE = 9, /* neighbourhood mask + residual draw */
-    MULO_PROF_OTHER = 10,     /* float32-path helpers */
+    MULO_PROF_OTHER = 10,     /* input shift; float32-path helpers */
     MULO_PROF_N = 11
 };
 MULO_API mulo_status mulo_profile(mulo_ctx *ctx, int32_t enable);

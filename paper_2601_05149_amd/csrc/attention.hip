@@ -37,7 +37,7 @@ struct AttnArgs {
 };
 
 template <int DH>
-__global__ __launch_bounds__(NTH) void k_attn_bf16(const AttnArgs a) {
+__global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     constexpr int KS = DH + 8;     // K tile row stride (bf16)
     constexpr int VS = BKV + 8;    // V^T tile row stride
     constexpr int NKK = DH / 16;   // k-steps of the first product

@@ -24,19 +24,18 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __hip_bfloat16 bf16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+enum { EPI_QK = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_V = 4 };
 
 struct GemmArgs {
     const bf16* A;        // [M, K]
-    const bf16* W0;       // QKV: wq | SWIGLU: w_gate | else: W [N, K]
-    const bf16* W1;       // QKV: wk | SWIGLU: w_up
-    const bf16* W2;       // QKV: wv
-    int M, N, K;          // N: output columns of the fused problem (QKV: 3d, SWIGLU: 2f)
+    const bf16* W0;       // QK: wq | SWIGLU: w_gate | else: W [N, K]
+    const bf16* W1;       // QK: wk | SWIGLU: w_up
+    int M, N, K;          // N: output columns of the fused problem (QK: 2d, SWIGLU: 2f)
     float* Cf;            // RESID: x [M, N] (+=) | LOGITS: logits [M, N]
-    bf16* Cb;             // SWIGLU: h [M, N/2] | QKV: q buffer
-    bf16* kc;             // QKV: caches
-    bf16* vc;
-    int d;                // QKV: model width (segment size)
+    bf16* Cb;             // SWIGLU: h [M, N/2] | QK: q buffer
+    bf16* kc;             // QK: K cache
+    bf16* vc;             // V: V^T cache
+    int d;                // QK: model width (segment size)
     RopeArgs ra;
 };
 
@@ -58,6 +57,7 @@ __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g));
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
+    constexpr bool SWAP = EPI == EPI_V;
     constexpr int NT = WGM * WGN * 64;
     constexpr int TM = BM / WGM, TN = BN / WGN, MB = TM / 32, NB = TN / 32;
     constexpr int LA = BM * 8 / NT, LB = BN * 8 / NT;  // 16-byte chunks per lane per stage
@@ -91,9 +91,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         const int nl = (tid >> 3) + i * (NT / 8);  // row of the B tile
         const bf16* base;
         int r;
-        if constexpr (EPI == EPI_QKV) {
+        if constexpr (EPI == EPI_QK) {
             const int seg = n0 / g.d;
-            base = seg == 0 ? g.W0 : (seg == 1 ? g.W1 : g.W2);
+            base = seg == 0 ? g.W0 : g.W1;
             r = n0 - seg * g.d + nl;
         } else if constexpr (EPI == EPI_SWIGLU) {
             // tile covers feed-forward columns [f0, f0 + BN/2); wave wn owns TN/2 of
@@ -138,6 +138,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
             *reinterpret_cast<u32x4*>(b + ((tid >> 3) + i * (NT / 8)) * LDS_STRIDE + kc8) = rb[i];
     };
 
+    // one k-step (16 of the 64 staged columns) of fragments, double-buffered in registers so
+    // that the LDS reads of step kk+1 are in flight while the MFMAs of step kk issue
+    bf16x8 af[2][MB], bfr[2][NB];
+    auto lfrag = [&](const bf16* a, const bf16* b, int kk, int slot) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+            af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + kk * 16);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 16);
+    };
+
     const int nk = g.K / BK;
     gload(0);
     sstore(0);
@@ -146,20 +158,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         if (kt + 1 < nk) gload(kt + 1);
         const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + l32) * LDS_STRIDE + lh * 8;
         const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + l32) * LDS_STRIDE + lh * 8;
+        lfrag(a, b, 0, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[MB], bfr[NB];
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + kk * 16);
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 16);
+            if (kk + 1 < BK / 16) lfrag(a, b, kk + 1, (kk + 1) & 1);
 #pragma unroll
             for (int i = 0; i < MB; ++i)
 #pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NB; ++j) {
+                    if constexpr (SWAP)   // D[n][m]: lanes run over rows of A (tokens)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+                    else                  // D[m][n]: lanes run over rows of W (output columns)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                }
         }
         if (kt + 1 < nk) sstore((kt + 1) & 1);
         __syncthreads();
@@ -186,26 +197,32 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
                     const int n = tile_n * (BN / 2) + wn * (TN / 2) + j * 32 + l32;
                     const float u = acc[i][j + NB / 2][r];
                     if (m < g.M && n < f) g.Cb[(int64_t)m * f + n] = __float2bfloat16(silu(v) * u);
-                } else {  // EPI_QKV
+                } else if constexpr (EPI == EPI_QK) {
+                    // rotary on adjacent column pairs (partner lane), q -> [B, nh, L, dh], k -> cache rows
                     const int n = n0 + nl, seg = n / g.d, c = n - seg * g.d;
                     const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
                     const float partner = __shfl_xor(v, 1);
                     if (m < g.M) {
                         const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
-                        float o = v;
-                        if (seg < 2) {
-                            const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)];
-                            const float sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
-                            o = (cc & 1) ? partner * sn + v * cs : v * cs - partner * sn;
-                        }
-                        const bf16 ob = __float2bfloat16(o);
-                        const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-                        if (seg == 0)
+                        const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)];
+                        const float sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
+                        const bf16 ob = __float2bfloat16((cc & 1) ? partner * sn + v * cs : v * cs - partner * sn);
+                        if (seg == 0) {
                             g.Cb[(((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc] = ob;
-                        else if (seg == 1)
+                        } else {
+                            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
                             g.kc[(hb * g.ra.max_seq + pos) * dh + cc] = ob;
-                        else
-                            g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = ob;
+                        }
+                    }
+                } else {  // EPI_V: operands swapped, so row index = output column, lane = token:
+                          // consecutive lanes write consecutive positions of a V^T cache row
+                    const int n = n0 + wn * TN + j * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+                    const int mm = m0 + wm * TM + i * 32 + l32;
+                    if (mm < g.M && n < g.N) {
+                        const int dh = g.ra.head_dim, hd = n / dh, cc = n % dh;
+                        const int b = mm / g.ra.L, pos = g.ra.P + mm % g.ra.L;
+                        const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+                        g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = __float2bfloat16(v);
                     }
                 }
             }
@@ -228,17 +245,12 @@ void run_gemm(const GemmArgs& g, int tiles_n, hipStream_t st) {
 }
 
 template <int EPI>
-void dispatch(const GemmArgs& g, int n_cols_per_tile_unit, hipStream_t st) {
-    // n_cols_per_tile_unit: problem columns (SWIGLU: feed-forward columns * 2) per BN
-    (void)n_cols_per_tile_unit;
-    const bool big = g.M >= 1024 && (EPI == EPI_QKV ? g.d % 256 == 0 : true);
-    if (big) {
-        const int tiles_n = (g.N + 255) / 256;
-        run_gemm<256, 256, 2, 2, EPI>(g, tiles_n, st);
-    } else {
-        const int tiles_n = (g.N + 127) / 128;
-        run_gemm<128, 128, 2, 2, EPI>(g, tiles_n, st);
-    }
+void dispatch(const GemmArgs& g, hipStream_t st) {
+    // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each: two per SIMD so one can
+    // issue MFMAs while the other waits on LDS); small ones: 128x128 tiles, 4 wavefronts
+    const bool big = g.M >= 1024 && (EPI == EPI_QK ? g.d % 256 == 0 : true);
+    if (big) run_gemm<256, 256, 4, 2, EPI>(g, (g.N + 255) / 256, st);
+    else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, st);
 }
 
 // ---------------------------------------------------------------- float32
@@ -287,16 +299,18 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
 void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
                           void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, hipStream_t st) {
     GemmArgs g{};
-    g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk; g.W2 = (const bf16*)wv;
-    g.M = M; g.N = 3 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.vc = (bf16*)v_cache;
-    g.d = d; g.ra = ra;
-    dispatch<EPI_QKV>(g, 0, st);
+    g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk;
+    g.M = M; g.N = 2 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.d = d; g.ra = ra;
+    dispatch<EPI_QK>(g, st);
+    GemmArgs v{};
+    v.A = (const bf16*)xh; v.W0 = (const bf16*)wv; v.M = M; v.N = d; v.K = d; v.vc = (bf16*)v_cache; v.ra = ra;
+    dispatch<EPI_V>(v, st);
 }
 
 void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, hipStream_t st) {
     GemmArgs g{};
     g.A = (const bf16*)a; g.W0 = (const bf16*)w; g.M = M; g.N = N; g.K = K; g.Cf = x;
-    dispatch<EPI_RESID>(g, 0, st);
+    dispatch<EPI_RESID>(g, st);
 }
 
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f, int d,
@@ -304,14 +318,14 @@ void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, voi
     GemmArgs g{};
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wg; g.W1 = (const bf16*)wu; g.M = M; g.N = 2 * f; g.K = d;
     g.Cb = (bf16*)h;
-    dispatch<EPI_SWIGLU>(g, 0, st);
+    dispatch<EPI_SWIGLU>(g, st);
 }
 
 void launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, int M, int V, int d,
                              hipStream_t st) {
     GemmArgs g{};
     g.A = (const bf16*)xh; g.W0 = (const bf16*)w; g.M = M; g.N = V; g.K = d; g.Cf = logits;
-    dispatch<EPI_LOGITS>(g, 0, st);
+    dispatch<EPI_LOGITS>(g, st);
 }
 
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc, int accumulate,

@@ -367,7 +367,7 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     // Step 2
     enqueue_upsample(ctx, B, h_blk, w, r, draft, input_is_probs, draft_tokens, thi, ctx->q_lo, ctx->q_row, nullptr);
     // Step 3: inputs [prev, x~_0 .. x~_{L-2}] so that logit row j is p of draft position j
-    { mulo_ctx* c = ctx; PROF(MULO_PROF_UPSAMPLE); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st); }
+    { mulo_ctx* c = ctx; PROF(MULO_PROF_OTHER); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st); }
     enqueue_forward(ctx, kv, B, L, P, ctx->inputs, nullptr, lg);
     // Steps 4-5 + residual re-draw
     DecideArgs a{};
