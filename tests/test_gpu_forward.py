@@ -95,8 +95,8 @@ def test_forward_small_bf16_chained_blocks():
     ek, ev = cache_error(dr, kv, B, P)
     # layer 0 sees identical inputs on both sides: its cache rows agree up to rare one-ulp bf16 flips
     # (a flipped input element moves every output of its row by a little, hence the absolute part)
-    tol_k = 2.0 ** -7 * (dr.k[0, :B, :P].double().abs() + 0.1)
-    tol_v = 2.0 ** -7 * (dr.v[0, :B, :P].double().abs() + 0.1)
+    tol_k = 2.0 ** -6 * (dr.k[0, :B, :P].double().abs() + 0.1)
+    tol_v = 2.0 ** -6 * (dr.v[0, :B, :P].double().abs() + 0.1)
     say("  layer-0 cache: K mismatching %.4f%% (max %.3g, beyond tol %d)  V mismatching %.4f%% (max %.3g, beyond tol %d)" % (
         100 * (ek[0] > 0).double().mean(), ek[0].max(), int((ek[0] > tol_k).sum()),
         100 * (ev[0] > 0).double().mean(), ev[0].max(), int((ev[0] > tol_v).sum())))
