@@ -2,9 +2,14 @@
 //
 // bf16 path: LDS-staged tiles feeding v_mfma_f32_32x32x16_bf16 (64-lane
 // wavefronts; both operands are K-contiguous so every lane fetches its 8-element
-// fragment with one 16-byte LDS read), float32 accumulation, and the element-wise
-// neighbours of each projection fused into the epilogue:
-//   QKV    -> rotary on adjacent pairs + scatter to q buffer / K cache / V^T cache
+// fragment with one 16-byte LDS read), float32 accumulation.  The MFMA operands
+// are exchanged (weight rows feed the MFMA rows, tokens run over the lanes) and
+// the weight rows are fetched with bits 2-3 of the row index swapped, so a lane
+// ends up owning one token and runs of 8 consecutive output columns: every
+// epilogue reads and writes 16-byte pieces.  Fused epilogues:
+//   Q|K    -> rotary on the adjacent pairs of a run (float4 table reads) + q buffer / K cache rows
+//   V      -> operands in order instead: a lane owns 8 consecutive tokens of one
+//             column = 16 contiguous bytes of the transposed V cache
 //   out, down -> residual add into the float32 stream
 //   gate|up   -> silu(gate) * up, gate and up columns interleaved inside a tile so
 //                that one lane owns both accumulators of a feed-forward column
@@ -55,9 +60,158 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
+// Source row of weight-tile row nl (fixed over the K loop) for each fused problem.
+template <int EPI, int BN, int TN>
+__device__ __forceinline__ const bf16* b_row(const GemmArgs& g, int n0, int tile_n, int nl) {
+    const bf16* base;
+    int r;
+    if constexpr (EPI == EPI_QK) {
+        const int seg = n0 / g.d;
+        base = seg == 0 ? g.W0 : g.W1;
+        r = n0 - seg * g.d + nl;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // tile covers feed-forward columns [f0, f0 + BN/2); the wavefront owning tile columns
+        // [w TN, (w+1) TN) gets TN/2 of them: gate rows in its first half, up rows in the second
+        const int f = g.N / 2, f0 = tile_n * (BN / 2);
+        const int w_ = nl / TN, within = nl % TN;
+        r = f0 + w_ * (TN / 2) + (within % (TN / 2));
+        r = r < f ? r : f - 1;
+        base = within >= TN / 2 ? g.W1 : g.W0;
+    } else {
+        base = g.W0;
+        r = n0 + nl;
+        r = r < g.N ? r : g.N - 1;
+    }
+    return base + (int64_t)r * g.K;
+}
+
+// Which tile row feeds MFMA row rho: bits 2 and 3 exchanged.  With it, accumulator r of a lane
+// covers, along the MFMA row axis, index 16*(r/8) + 8*lh + r%8: two runs of 8 consecutive indices
+// per 32x32 block, so every lane stores 16-byte (bf16) or 2 x 16-byte (float) pieces.
+__device__ __forceinline__ int kperm(int l32) { return (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1); }
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8s;
+
+// Fused epilogues.  acc[i][j] is the 32x32 block (i, j) of the wavefront's TM x TN tile whose corner
+// is (m0 + wm TM, n0 + wn TN).  All projections but V run with the MFMA operands exchanged, so a
+// lane owns ONE token row (m = ... + l32) and, per block, the column runs [16 g + 8 lh, +8), g = 0, 1
+// (accumulators 8 g .. 8 g + 7).  The V projection keeps the operands in order: a lane owns one
+// output column and runs of 8 consecutive tokens, which are contiguous in the transposed V cache.
+template <int EPI, int BN, int TM, int TN, int MB, int NB>
+__device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB], int m0, int n0, int tile_n,
+                                         int wm, int wn, int l32, int lh) {
+    constexpr int NBE = EPI == EPI_SWIGLU ? NB / 2 : NB;   // gate blocks only: up blocks are consumed with them
+    static_for<MB>([&](auto ic) {
+        static_for<NBE>([&](auto jc) {
+            constexpr int i = decltype(ic)::value, j = decltype(jc)::value;
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = acc[i][j][g2 * 8 + e];
+                if constexpr (EPI == EPI_V) {
+                    const int n = n0 + wn * TN + j * 32 + l32;                       // output column (head, cc)
+                    const int mb = m0 + wm * TM + i * 32 + g2 * 16 + lh * 8;         // first of 8 tokens
+                    if (n < g.N && mb < g.M) {
+                        const int dh = g.ra.head_dim, hd = n / dh, cc = n % dh;
+                        const int b = mb / g.ra.L, jj = mb % g.ra.L;
+                        const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+                        bf16* dst = g.vc + (hb * dh + cc) * g.ra.max_seq + g.ra.P + jj;
+                        if (((g.ra.P | g.ra.L) & 7) == 0) {                          // aligned run inside one sequence
+                            bf16x8s o;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+                            *reinterpret_cast<bf16x8s*>(dst) = o;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const int m = mb + e;
+                                if (m < g.M) {
+                                    const int b2 = m / g.ra.L, j2 = m % g.ra.L;
+                                    const int64_t hb2 = ((int64_t)g.ra.layer * g.ra.max_batch + b2) * g.ra.n_heads + hd;
+                                    g.vc[(hb2 * dh + cc) * g.ra.max_seq + g.ra.P + j2] = __float2bfloat16(v[e]);
+                                }
+                            }
+                        }
+                    }
+                } else {
+                    const int m = m0 + wm * TM + i * 32 + l32;                       // token row of this lane
+                    const int cl = j * 32 + g2 * 16 + lh * 8;                        // column run inside the wave tile
+                    if (m < g.M) {
+                        if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
+                            const int n = n0 + wn * TN + cl;
+                            float* dst = g.Cf + (int64_t)m * g.N + n;
+                            if (n + 8 <= g.N) {
+                                f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+                                if constexpr (EPI == EPI_RESID) {
+                                    lo += *reinterpret_cast<const f32x4*>(dst);
+                                    hi += *reinterpret_cast<const f32x4*>(dst + 4);
+                                }
+                                *reinterpret_cast<f32x4*>(dst) = lo;
+                                *reinterpret_cast<f32x4*>(dst + 4) = hi;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v[e] : v[e];
+                            }
+                        } else if constexpr (EPI == EPI_SWIGLU) {
+                            const int f = g.N / 2;
+                            const int n = tile_n * (BN / 2) + wn * (TN / 2) + cl;
+                            bf16* dst = g.Cb + (int64_t)m * f + n;
+                            float h[8];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) h[e] = silu(v[e]) * acc[i][j + NB / 2][g2 * 8 + e];
+                            if (n + 8 <= f) {
+                                bf16x8s o;
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) o[e] = (__bf16)h[e];
+                                *reinterpret_cast<bf16x8s*>(dst) = o;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (n + e < f) dst[e] = __float2bfloat16(h[e]);
+                            }
+                        } else {  // EPI_QK: rotary on the 4 adjacent pairs of the run, q -> [B, nh, L, dh], k -> cache row
+                            const int n = n0 + wn * TN + cl, seg = n / g.d, c = n - seg * g.d;
+                            const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
+                            const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
+                            const f32x4 cs = *reinterpret_cast<const f32x4*>(g.ra.cos + (int64_t)pos * (dh / 2) + (cc >> 1));
+                            const f32x4 sn = *reinterpret_cast<const f32x4*>(g.ra.sin + (int64_t)pos * (dh / 2) + (cc >> 1));
+                            bf16x8s o;
+#pragma unroll
+                            for (int pr = 0; pr < 4; ++pr) {
+                                o[2 * pr] = (__bf16)(v[2 * pr] * cs[pr] - v[2 * pr + 1] * sn[pr]);
+                                o[2 * pr + 1] = (__bf16)(v[2 * pr] * sn[pr] + v[2 * pr + 1] * cs[pr]);
+                            }
+                            bf16* dst;
+                            if (seg == 0) {
+                                dst = g.Cb + (((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc;
+                            } else {
+                                const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+                                dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
+                            }
+                            *reinterpret_cast<bf16x8s*>(dst) = o;
+                        }
+                    }
+                }
+            }
+        });
+    });
+}
+
+template <bool SWAP>
+__device__ __forceinline__ f32x16 mma(const bf16x8& a, const bf16x8& b, const f32x16& c) {
+    if constexpr (SWAP)   // D[n][m]: MFMA rows = weight rows (output columns), lanes = tokens
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
+    else                  // D[m][n]: MFMA rows = tokens, lanes = output columns (V projection)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---- BM x BN x 64 tiles, double-buffered LDS, one barrier per K-tile ---------------------------
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
-    constexpr bool SWAP = EPI == EPI_V;
+    constexpr bool SWAP = EPI != EPI_V;
     constexpr int NT = WGM * WGN * 64;
     constexpr int TM = BM / WGM, TN = BN / WGN, MB = TM / 32, NB = TN / 32;
     constexpr int LA = BM * 8 / NT, LB = BN * 8 / NT;  // 16-byte chunks per lane per stage
@@ -70,13 +224,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN, l32 = lane & 31, lh = lane >> 5;
-
+    const int fra = SWAP ? l32 : kperm(l32), frb = SWAP ? kperm(l32) : l32;   // fragment rows (MFMA-row operand permuted)
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
-    const int m0 = tile_m * BM;
-    const int n0 = tile_n * BN;  // first fused output column of this tile
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    // per-lane source rows of the two operand tiles (fixed over the K loop)
     const int kc8 = (tid & 7) * 8;
     const bf16* pa[LA];
     const bf16* pb[LB];
@@ -87,30 +239,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         pa[i] = g.A + (int64_t)r * g.K + kc8;
     }
 #pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int nl = (tid >> 3) + i * (NT / 8);  // row of the B tile
-        const bf16* base;
-        int r;
-        if constexpr (EPI == EPI_QK) {
-            const int seg = n0 / g.d;
-            base = seg == 0 ? g.W0 : g.W1;
-            r = n0 - seg * g.d + nl;
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            // tile covers feed-forward columns [f0, f0 + BN/2); wave wn owns TN/2 of
-            // them, gate rows in its first NB/2 blocks and up rows in the rest
-            const int f = g.N / 2, f0 = tile_n * (BN / 2);
-            const int w_ = nl / TN, within = nl % TN;
-            const bool up = within >= TN / 2;
-            r = f0 + w_ * (TN / 2) + (within % (TN / 2));
-            r = r < f ? r : f - 1;
-            base = up ? g.W1 : g.W0;
-        } else {
-            base = g.W0;
-            r = n0 + nl;
-            r = r < g.N ? r : g.N - 1;
-        }
-        pb[i] = base + (int64_t)r * g.K + kc8;
-    }
+    for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, (tid >> 3) + i * (NT / 8)) + kc8;
 
     f32x16 acc[MB][NB];
 #pragma unroll
@@ -137,10 +266,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         for (int i = 0; i < LB; ++i)
             *reinterpret_cast<u32x4*>(b + ((tid >> 3) + i * (NT / 8)) * LDS_STRIDE + kc8) = rb[i];
     };
-
-    // one k-step (16 of the 64 staged columns) of fragments, double-buffered in registers so
-    // that the LDS reads of step kk+1 are in flight while the MFMAs of step kk issue
-    bf16x8 af[2][MB], bfr[2][NB];
+    bf16x8 af[2][MB], bfr[2][NB];   // fragments of one k-step, double-buffered in registers
     auto lfrag = [&](const bf16* a, const bf16* b, int kk, int slot) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
@@ -156,8 +282,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) gload(kt + 1);
-        const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + l32) * LDS_STRIDE + lh * 8;
-        const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + l32) * LDS_STRIDE + lh * 8;
+        const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
+        const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
         lfrag(a, b, 0, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -165,69 +291,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
 #pragma unroll
             for (int i = 0; i < MB; ++i)
 #pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    if constexpr (SWAP)   // D[n][m]: lanes run over rows of A (tokens)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-                    else                  // D[m][n]: lanes run over rows of W (output columns)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-                }
+                for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[kk & 1][i], bfr[kk & 1][j], acc[i][j]);
         }
         if (kt + 1 < nk) sstore((kt + 1) & 1);
         __syncthreads();
     }
-
-    // ---- epilogue.  Accumulator r of a 32x32 block: row (r/4)*8 + lh*4 + r%4, column l32.
-    constexpr int NBE = EPI == EPI_SWIGLU ? NB / 2 : NB;   // gate blocks only: up blocks are consumed with them
-    static_for<MB>([&](auto ic) {
-        static_for<NBE>([&](auto jc) {
-            constexpr int i = decltype(ic)::value, j = decltype(jc)::value;
-            const int nl = wn * TN + j * 32 + l32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * TM + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-                const float v = acc[i][j][r];
-                if constexpr (EPI == EPI_RESID) {
-                    const int n = n0 + nl;
-                    if (m < g.M && n < g.N) g.Cf[(int64_t)m * g.N + n] += v;
-                } else if constexpr (EPI == EPI_LOGITS) {
-                    const int n = n0 + nl;
-                    if (m < g.M && n < g.N) g.Cf[(int64_t)m * g.N + n] = v;
-                } else if constexpr (EPI == EPI_SWIGLU) {
-                    const int f = g.N / 2;
-                    const int n = tile_n * (BN / 2) + wn * (TN / 2) + j * 32 + l32;
-                    const float u = acc[i][j + NB / 2][r];
-                    if (m < g.M && n < f) g.Cb[(int64_t)m * f + n] = __float2bfloat16(silu(v) * u);
-                } else if constexpr (EPI == EPI_QK) {
-                    // rotary on adjacent column pairs (partner lane), q -> [B, nh, L, dh], k -> cache rows
-                    const int n = n0 + nl, seg = n / g.d, c = n - seg * g.d;
-                    const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
-                    const float partner = __shfl_xor(v, 1);
-                    if (m < g.M) {
-                        const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
-                        const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)];
-                        const float sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
-                        const bf16 ob = __float2bfloat16((cc & 1) ? partner * sn + v * cs : v * cs - partner * sn);
-                        if (seg == 0) {
-                            g.Cb[(((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc] = ob;
-                        } else {
-                            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-                            g.kc[(hb * g.ra.max_seq + pos) * dh + cc] = ob;
-                        }
-                    }
-                } else {  // EPI_V: operands swapped, so row index = output column, lane = token:
-                          // consecutive lanes write consecutive positions of a V^T cache row
-                    const int n = n0 + wn * TN + j * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-                    const int mm = m0 + wm * TM + i * 32 + l32;
-                    if (mm < g.M && n < g.N) {
-                        const int dh = g.ra.head_dim, hd = n / dh, cc = n % dh;
-                        const int b = mm / g.ra.L, pos = g.ra.P + mm % g.ra.L;
-                        const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-                        g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = __float2bfloat16(v);
-                    }
-                }
-            }
-        });
-    });
+    epilogue<EPI, BN, TM, TN, MB, NB>(g, acc, m0, n0, tile_n, wm, wn, l32, lh);
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
@@ -246,8 +315,7 @@ void run_gemm(const GemmArgs& g, int tiles_n, hipStream_t st) {
 
 template <int EPI>
 void dispatch(const GemmArgs& g, hipStream_t st) {
-    // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each: two per SIMD so one can
-    // issue MFMAs while the other waits on LDS); small ones: 128x128 tiles, 4 wavefronts
+    // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     const bool big = g.M >= 1024 && (EPI == EPI_QK ? g.d % 256 == 0 : true);
     if (big) run_gemm<256, 256, 4, 2, EPI>(g, (g.N + 255) / 256, st);
     else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, st);
