@@ -226,15 +226,23 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
     const int64_t row = blockIdx.x;
     const int b = row / a.L, t = row % a.L, tid = threadIdx.x;
     const float* z = a.logits + row * a.V;
+    // the scalar gathers (draft token -> its logit and its draft probability) are issued first, so that
+    // their chained latency is hidden behind the streaming of the row
+    const int tok = clamp_tok(a.draft_tokens[row], a.V);
+    float ztok = 0.f, qt = 0.f;
+    if (tid == 0) {
+        const int qr = a.q_row ? a.q_row[t] : t;
+        qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
+        ztok = z[tok];
+    }
     RowRegs<NV4> rr;
     float m, inv;
     row_stats<NV4>(z, a.V, rr, red, m, inv);
     if (a.p_probs) row_write_probs<NV4>(z, a.p_probs + row * a.V, a.V, rr, m, inv);
 
-    const int tok = clamp_tok(a.draft_tokens[row], a.V);
     float pbar;
     if (a.pool_k <= 1) {
-        pbar = prob(z[tok], m, inv);
+        pbar = prob(ztok, m, inv);
     } else {  // Eq. 3: pooled mass over the codebook neighbours of the draft token
         float acc = 0.f;
         for (int i = tid; i < a.pool_k; i += TPB)
@@ -242,8 +250,6 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
         pbar = block_sum(acc, red);
     }
     if (tid == 0) {
-        const int qr = a.q_row ? a.q_row[t] : t;
-        const float qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
         const uint32_t w0 = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24, a.key0, a.key1);
         const float u = (float)(w0 >> 8) * 5.9604644775390625e-08f;  // 2^-24, exact
         const float uq = __fmul_rn(u, qt);

@@ -32,22 +32,48 @@ __global__ __launch_bounds__(TPB) void k_embed(const T* __restrict__ embed, cons
     for (int c = threadIdx.x; c < d; c += TPB) x[m * d + c] = ld(src, c);
 }
 
-// out = x / sqrt(mean(x^2) + eps) * gain, one workgroup per row, float32 inside
-template <typename T>
+// out = x / sqrt(mean(x^2) + eps) * gain, one workgroup per row, float32 inside.  The row is read
+// once with 16-byte loads and kept in registers (d <= 256 * 4 * NV4); NV4 == 0 re-reads it instead.
+template <typename T, int NV4>
 __global__ __launch_bounds__(TPB) void k_rmsnorm(const float* __restrict__ x, const T* __restrict__ gain,
                                                  T* __restrict__ out, int d, float eps) {
     __shared__ float red[TPB / 64];
     const int64_t m = blockIdx.x;
     const float* xr = x + m * d;
+    const int nv4 = d >> 2, tid = threadIdx.x;
+    float4 v[NV4 > 0 ? NV4 : 1];
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += TPB) { const float v = xr[c]; ss += v * v; }
+    if constexpr (NV4 > 0) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            const int idx = i * TPB + tid;
+            v[i] = idx < nv4 ? reinterpret_cast<const float4*>(xr)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            ss += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+        }
+    } else {
+        for (int c = tid; c < d; c += TPB) { const float t = xr[c]; ss += t * t; }
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
     ss = (red[0] + red[1]) + (red[2] + red[3]);
     const float sc = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += TPB) st(out, m * d + c, xr[c] * sc * ld(gain, c));
+    if constexpr (NV4 > 0) {
+#pragma unroll
+        for (int i = 0; i < NV4; ++i) {
+            const int idx = i * TPB + tid;
+            if (idx < nv4) {
+                const int c = idx * 4;
+                st(out, m * d + c, v[i].x * sc * ld(gain, c));
+                st(out, m * d + c + 1, v[i].y * sc * ld(gain, c + 1));
+                st(out, m * d + c + 2, v[i].z * sc * ld(gain, c + 2));
+                st(out, m * d + c + 3, v[i].w * sc * ld(gain, c + 3));
+            }
+        }
+    } else {
+        for (int c = tid; c < d; c += TPB) st(out, m * d + c, xr[c] * sc * ld(gain, c));
+    }
 }
 
 // float32 path: rotary on adjacent pairs of q and k, q -> [B, nh, L, dh],
@@ -97,14 +123,18 @@ void launch_embed(const void* embed, int dtype, const int32_t* tok, const void* 
                            (const float*)in_embeds, x, d, V);
 }
 
+template <typename T>
+static void rmsnorm_dispatch(const float* x, const T* gain, T* out, int M, int d, float eps, hipStream_t s) {
+    if ((d & 3) == 0 && d <= 1024) hipLaunchKernelGGL((k_rmsnorm<T, 1>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
+    else if ((d & 3) == 0 && d <= 4096) hipLaunchKernelGGL((k_rmsnorm<T, 4>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
+    else if ((d & 3) == 0 && d <= 8192) hipLaunchKernelGGL((k_rmsnorm<T, 8>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
+    else hipLaunchKernelGGL((k_rmsnorm<T, 0>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
+}
+
 void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps,
                     hipStream_t s) {
-    if (dtype == 1)
-        hipLaunchKernelGGL(k_rmsnorm<__hip_bfloat16>, dim3(M), dim3(TPB), 0, s, x,
-                           (const __hip_bfloat16*)gain, (__hip_bfloat16*)out, d, eps);
-    else
-        hipLaunchKernelGGL(k_rmsnorm<float>, dim3(M), dim3(TPB), 0, s, x, (const float*)gain, (float*)out,
-                           d, eps);
+    if (dtype == 1) rmsnorm_dispatch(x, (const __hip_bfloat16*)gain, (__hip_bfloat16*)out, M, d, eps, s);
+    else rmsnorm_dispatch(x, (const float*)gain, (float*)out, M, d, eps, s);
 }
 
 void launch_rope_append_f32(const float* qkv, float* q_out, float* k_cache, float* v_cache, int M, int d,

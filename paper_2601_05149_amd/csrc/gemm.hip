@@ -41,6 +41,7 @@ struct GemmArgs {
     bf16* kc;             // QK: K cache
     bf16* vc;             // V: V^T cache
     int d;                // QK: model width (segment size)
+    int tiles_n;          // column tiles of the launch (set by the launcher)
     RopeArgs ra;
 };
 
@@ -225,30 +226,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN, l32 = lane & 31, lh = lane >> 5;
     const int fra = SWAP ? l32 : kperm(l32), frb = SWAP ? kperm(l32) : l32;   // fragment rows (MFMA-row operand permuted)
-    const int tiles_m = (g.M + BM - 1) / BM;
-    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
+    // persistent workgroups: each walks the output tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+    const int tiles_m = (g.M + BM - 1) / BM, total_tiles = tiles_m * g.tiles_n;
+    int tile = blockIdx.x, tile_n = 0, m0 = 0, n0 = 0;
     const int kc8 = (tid & 7) * 8;
     const bf16* pa[LA];
     const bf16* pb[LB];
+    auto setup = [&](int t) {   // operand rows of tile t (fixed over its K loop)
+        tile_n = t / tiles_m;
+        m0 = (t % tiles_m) * BM;
+        n0 = tile_n * BN;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        int r = m0 + (tid >> 3) + i * (NT / 8);
-        r = r < g.M ? r : g.M - 1;
-        pa[i] = g.A + (int64_t)r * g.K + kc8;
-    }
+        for (int i = 0; i < LA; ++i) {
+            int r = m0 + (tid >> 3) + i * (NT / 8);
+            r = r < g.M ? r : g.M - 1;
+            pa[i] = g.A + (int64_t)r * g.K + kc8;
+        }
 #pragma unroll
-    for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, (tid >> 3) + i * (NT / 8)) + kc8;
+        for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, (tid >> 3) + i * (NT / 8)) + kc8;
+    };
 
     f32x16 acc[MB][NB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
     u32x4 ra[LA], rb[LB];
     auto gload = [&](int kt) {
 #pragma unroll
@@ -277,30 +275,59 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     };
 
     const int nk = g.K / BK;
+    setup(tile);
     gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
-        const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
-        const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
-        lfrag(a, b, 0, 0);
+    while (true) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) lfrag(a, b, kk + 1, (kk + 1) & 1);
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
+            for (int j = 0; j < NB; ++j)
 #pragma unroll
-                for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[kk & 1][i], bfr[kk & 1][j], acc[i][j]);
-        }
-        if (kt + 1 < nk) sstore((kt + 1) & 1);
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        sstore(0);
         __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt + 1 < nk) gload(kt + 1);
+            const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
+            const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
+            lfrag(a, b, 0, 0);
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                if (kk + 1 < BK / 16) lfrag(a, b, kk + 1, (kk + 1) & 1);
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[kk & 1][i], bfr[kk & 1][j], acc[i][j]);
+            }
+            if (kt + 1 < nk) sstore((kt + 1) & 1);
+            __syncthreads();
+        }
+        // the first K-tile of the next output tile is fetched while this tile's epilogue runs
+        const int e_m0 = m0, e_n0 = n0, e_tile_n = tile_n;
+        tile += gridDim.x;
+        const bool more = tile < total_tiles;
+        if (more) {
+            setup(tile);
+            gload(0);
+        }
+        epilogue<EPI, BN, TM, TN, MB, NB>(g, acc, e_m0, e_n0, e_tile_n, wm, wn, l32, lh);
+        if (!more) break;
     }
-    epilogue<EPI, BN, TM, TN, MB, NB>(g, acc, m0, n0, tile_n, wm, wn, l32, lh);
+}
+
+static int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
-void run_gemm(const GemmArgs& g, int tiles_n, hipStream_t st) {
+void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
     auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI>;
     const size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16);
     static bool attr_set = false;  // one context per process configures each instantiation once
@@ -309,16 +336,18 @@ void run_gemm(const GemmArgs& g, int tiles_n, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    const int tiles_m = (g.M + BM - 1) / BM;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WGM * WGN * 64), lds, st, g);
+    const int tiles_m = (g.M + BM - 1) / BM, total = tiles_m * tiles_n;
+    const int resident = cu_count() * blocks_per_cu;
+    g.tiles_n = tiles_n;
+    hipLaunchKernelGGL(kern, dim3(total < resident ? total : resident), dim3(WGM * WGN * 64), lds, st, g);
 }
 
 template <int EPI>
 void dispatch(const GemmArgs& g, hipStream_t st) {
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     const bool big = g.M >= 1024 && (EPI == EPI_QK ? g.d % 256 == 0 : true);
-    if (big) run_gemm<256, 256, 4, 2, EPI>(g, (g.N + 255) / 256, st);
-    else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, st);
+    if (big) run_gemm<256, 256, 4, 2, EPI>(g, (g.N + 255) / 256, 1, st);
+    else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, 2, st);
 }
 
 // ---------------------------------------------------------------- float32
