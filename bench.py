@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--sigma", type=float, default=None, help="draft-logit noise std (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB read + 1 GiB write element-wise kernel (scale for HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
@@ -82,6 +84,15 @@ def main():
     from workloads import generators as G
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"read_bytes": src.numel() * 4, "write_bytes": dst.numel() * 4,
+                                             "launches": 3}}), flush=True)
+        return
     mulo.load_library()                   # fails loudly if the HIP library is not built
     dev = "cuda:0"
     c = WC.get(a.workload)

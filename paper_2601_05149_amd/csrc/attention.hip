@@ -49,7 +49,21 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     bf16* sV = sK + 2 * BKV * KS;               // [2][DH][VS]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
-    const int j0 = blockIdx.x * BQ, hd = blockIdx.y, b = blockIdx.z;
+    // Workgroup id -> (query tile, head).  Consecutive ids go to consecutive XCDs, each with its own L2:
+    // all query tiles of one (batch, head) are given to ONE XCD, next to each other in its dispatch
+    // order, so that they stream that head's K and V through the same L2 side by side (the cache rows
+    // are fetched from memory once per head instead of once per query tile).  Long tiles go first.
+    const int qtiles = (a.L + BQ - 1) / BQ, nbh = a.B * a.nh;
+    int qt, bh;
+    if ((nbh & 7) == 0) {
+        const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+        qt = qtiles - 1 - s % qtiles;
+        bh = (s / qtiles) * 8 + xcd;
+    } else {
+        qt = qtiles - 1 - blockIdx.x % qtiles;
+        bh = blockIdx.x / qtiles;
+    }
+    const int j0 = qt * BQ, hd = bh % a.nh, b = bh / a.nh;
     const int64_t hb = ((int64_t)a.layer * a.max_batch + b) * a.nh + hd;
     const bf16* kbase = a.kc + hb * a.max_seq * DH;
     const bf16* vbase = a.vc + hb * DH * a.max_seq;
@@ -267,7 +281,7 @@ void run_attn(const AttnArgs& a, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3((a.L + BQ - 1) / BQ, a.nh, a.B), dim3(NTH), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B), dim3(NTH), lds, st, a);
 }
 
 }  // namespace

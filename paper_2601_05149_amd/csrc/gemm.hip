@@ -226,15 +226,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN, l32 = lane & 31, lh = lane >> 5;
     const int fra = SWAP ? l32 : kperm(l32), frb = SWAP ? kperm(l32) : l32;   // fragment rows (MFMA-row operand permuted)
-    // persistent workgroups: each walks the output tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+    // Persistent workgroups.  Workgroup b runs on XCD b % 8 (round-robin dispatch), and each XCD has
+    // its own L2, so the tile sequence is cut into one contiguous chunk per XCD and the sequence
+    // itself walks groups of GW column tiles row by row: the workgroups of one XCD then work, at any
+    // moment, on a near-square patch of output tiles and share its operand rows through that L2.
+    constexpr int GW = 8;
     const int tiles_m = (g.M + BM - 1) / BM, total_tiles = tiles_m * g.tiles_n;
-    int tile = blockIdx.x, tile_n = 0, m0 = 0, n0 = 0;
+    const int nxcd = (gridDim.x & 7) == 0 ? 8 : 1;
+    const int tile_stride = gridDim.x / nxcd, chunk = (total_tiles + nxcd - 1) / nxcd;
+    const int chunk_base = (blockIdx.x % nxcd) * chunk;
+    const int chunk_len = total_tiles - chunk_base < chunk ? total_tiles - chunk_base : chunk;   // may be <= 0
+    int tile = blockIdx.x / nxcd, tile_n = 0, m0 = 0, n0 = 0;
     const int kc8 = (tid & 7) * 8;
     const bf16* pa[LA];
     const bf16* pb[LB];
-    auto setup = [&](int t) {   // operand rows of tile t (fixed over its K loop)
-        tile_n = t / tiles_m;
-        m0 = (t % tiles_m) * BM;
+    auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
+        const int t = chunk_base + local, grp = t / (tiles_m * GW), rem = t - grp * tiles_m * GW;
+        const int gw = g.tiles_n - grp * GW < GW ? g.tiles_n - grp * GW : GW;
+        tile_n = grp * GW + rem % gw;
+        m0 = (rem / gw) * BM;
         n0 = tile_n * BN;
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
@@ -275,6 +285,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     };
 
     const int nk = g.K / BK;
+    if (tile >= chunk_len) return;   // uniform over the workgroup, before any barrier
     setup(tile);
     gload(0);
     while (true) {
@@ -304,8 +315,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         }
         // the first K-tile of the next output tile is fetched while this tile's epilogue runs
         const int e_m0 = m0, e_n0 = n0, e_tile_n = tile_n;
-        tile += gridDim.x;
-        const bool more = tile < total_tiles;
+        tile += tile_stride;
+        const bool more = tile < chunk_len;
         if (more) {
             setup(tile);
             gload(0);
