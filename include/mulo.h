@@ -59,7 +59,7 @@ typedef enum { MULO_F32 = 0, MULO_BF16 = 1 } mulo_dtype;
  * attention with n_heads * head_dim == d_model, SwiGLU feed-forward, no biases).
  * max_block is the largest draft block L, max_batch the largest batch B and
  * max_seq the number of cache rows per sequence (prefix + image tokens).
- * Limits: head_dim 64 or 128 for MULO_BF16; d_model a multiple of 128, d_ffn of 64,
+ * Limits: head_dim 64 or 128 for MULO_BF16; d_model a multiple of 128, d_ffn of 64 (and at least 128),
  * max_seq of 8 and max_block of 4 for MULO_BF16; vocab a multiple of 4 and at most 262144. */
 typedef struct {
     int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;

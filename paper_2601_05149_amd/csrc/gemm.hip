@@ -45,8 +45,6 @@ struct GemmArgs {
     RopeArgs ra;
 };
 
-constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per tile row: 144 B keeps 16-byte reads conflict-free
 
 // compile-time loop: the body sees its index as a constant, so accumulator arrays
 // indexed by it stay in registers whatever the unroller decides
@@ -210,13 +208,14 @@ __device__ __forceinline__ f32x16 mma(const bf16x8& a, const bf16x8& b, const f3
 }
 
 // ---- BM x BN x 64 tiles, double-buffered LDS, one barrier per K-tile ---------------------------
-template <int BM, int BN, int WGM, int WGN, int EPI>
-__global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
+__global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536) ? 1 : 2) void k_gemm_bf16(const GemmArgs g) {
+    constexpr int BK = BKT, LDS_STRIDE = BKT + 8, CPR = BKT / 8;   // 16-byte chunks per tile row
     constexpr bool SWAP = EPI != EPI_V;
     constexpr int NT = WGM * WGN * 64;
     constexpr int TM = BM / WGM, TN = BN / WGN, MB = TM / 32, NB = TN / 32;
-    constexpr int LA = BM * 8 / NT, LB = BN * 8 / NT;  // 16-byte chunks per lane per stage
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads");
+    constexpr int LA = BM * CPR / NT, LB = BN * CPR / NT;  // 16-byte chunks per lane per stage
+    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads");
     static_assert(EPI != EPI_SWIGLU || NB % 2 == 0, "swiglu needs an even number of column blocks");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -237,7 +236,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
     const int chunk_base = (blockIdx.x % nxcd) * chunk;
     const int chunk_len = total_tiles - chunk_base < chunk ? total_tiles - chunk_base : chunk;   // may be <= 0
     int tile = blockIdx.x / nxcd, tile_n = 0, m0 = 0, n0 = 0;
-    const int kc8 = (tid & 7) * 8;
+    const int kc8 = (tid % CPR) * 8, trow = tid / CPR;
     const bf16* pa[LA];
     const bf16* pb[LB];
     auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
@@ -248,12 +247,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
         n0 = tile_n * BN;
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
-            int r = m0 + (tid >> 3) + i * (NT / 8);
+            int r = m0 + trow + i * (NT / CPR);
             r = r < g.M ? r : g.M - 1;
             pa[i] = g.A + (int64_t)r * g.K + kc8;
         }
 #pragma unroll
-        for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, (tid >> 3) + i * (NT / 8)) + kc8;
+        for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, trow + i * (NT / CPR)) + kc8;
     };
 
     f32x16 acc[MB][NB];
@@ -264,15 +263,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(pb[i] + kt * BK);
     };
+    const int nk = g.K / BK;
     auto sstore = [&](int buf) {
         bf16* a = sA + buf * BM * LDS_STRIDE;
         bf16* b = sB + buf * BN * LDS_STRIDE;
 #pragma unroll
         for (int i = 0; i < LA; ++i)
-            *reinterpret_cast<u32x4*>(a + ((tid >> 3) + i * (NT / 8)) * LDS_STRIDE + kc8) = ra[i];
+            *reinterpret_cast<u32x4*>(a + (trow + i * (NT / CPR)) * LDS_STRIDE + kc8) = ra[i];
 #pragma unroll
         for (int i = 0; i < LB; ++i)
-            *reinterpret_cast<u32x4*>(b + ((tid >> 3) + i * (NT / 8)) * LDS_STRIDE + kc8) = rb[i];
+            *reinterpret_cast<u32x4*>(b + (trow + i * (NT / CPR)) * LDS_STRIDE + kc8) = rb[i];
     };
     bf16x8 af[2][MB], bfr[2][NB];   // fragments of one k-step, double-buffered in registers
     auto lfrag = [&](const bf16* a, const bf16* b, int kk, int slot) {
@@ -284,10 +284,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
             bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 16);
     };
 
-    const int nk = g.K / BK;
+    // Pipeline over the flattened sequence of K-steps of all this workgroup's tiles.  While step s is
+    // multiplied out of LDS buffer s & 1, step s+1 is in flight into the staging registers; at the end
+    // of the iteration it is written to the other buffer and step s+2 is requested AT ONCE, before the
+    // barrier: the requests then have the barrier wait and the whole next multiply phase to complete
+    // (their latency, about 1500 cycles, is most of a multiply phase), and the burst that fills the
+    // memory pipeline's queue stalls wavefronts that are about to wait at the barrier anyway.  Near the
+    // end of a tile the requests run ahead into the next tile, whose first step is staged while this
+    // tile's epilogue runs.  The launcher guarantees nk >= 2.
     if (tile >= chunk_len) return;   // uniform over the workgroup, before any barrier
     setup(tile);
     gload(0);
+    sstore(0);
+    gload(1);
+    __syncthreads();
+    int gs = 0;   // steps done so far: buffer parity
     while (true) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
@@ -295,12 +306,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
             for (int j = 0; j < NB; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-        sstore(0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            if (kt + 1 < nk) gload(kt + 1);
-            const bf16* a = sA + (kt & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
-            const bf16* b = sB + (kt & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
+        int e_m0 = m0, e_n0 = n0, e_tile_n = tile_n;
+        bool more = true;
+        auto multiply = [&](int step) {   // K-step `step` out of LDS buffer step & 1
+            const bf16* a = sA + (step & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
+            const bf16* b = sB + (step & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
             lfrag(a, b, 0, 0);
 #pragma unroll
             for (int kk = 0; kk < BK / 16; ++kk) {
@@ -310,16 +320,39 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_gemm_bf16(const GemmArgs g) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[kk & 1][i], bfr[kk & 1][j], acc[i][j]);
             }
-            if (kt + 1 < nk) sstore((kt + 1) & 1);
+        };
+        int kt = 0;
+        // steady state: one scheduling region per K-step.  The first half of the MFMAs runs with the
+        // fragment reads; in the second half every staging register is written to LDS as soon as its
+        // load (requested one iteration ago) is there and is at once requested again for step kt + 2.
+        for (; kt < nk - 2; ++kt, ++gs) {
+            multiply(gs);
+            sstore((gs + 1) & 1);
+            gload(kt + 2);
+            {
+                constexpr int NL = LA + LB, NM = MB * NB * (BK / 16);
+                constexpr int TAIL = NM >= 4 * NL ? 2 : 1, HEAD = NM - TAIL * NL;
+                if (HEAD > 0) __builtin_amdgcn_sched_group_barrier(0x008, HEAD > 0 ? HEAD : 1, 0);
+#pragma unroll
+                for (int i = 0; i < NL; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);      // LDS write of staging register i
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);      // its next global load
+                    __builtin_amdgcn_sched_group_barrier(0x008, TAIL, 0);
+                }
+            }
             __syncthreads();
         }
-        // the first K-tile of the next output tile is fetched while this tile's epilogue runs
-        const int e_m0 = m0, e_n0 = n0, e_tile_n = tile_n;
-        tile += tile_stride;
-        const bool more = tile < chunk_len;
-        if (more) {
-            setup(tile);
-            gload(0);
+        for (; kt < nk; ++kt, ++gs) {   // last two steps of the tile: the requests move on to the next tile
+            multiply(gs);
+            if (kt == nk - 2) {
+                e_m0 = m0; e_n0 = n0; e_tile_n = tile_n;
+                tile += tile_stride;
+                more = tile < chunk_len;
+                if (more) setup(tile);
+            }
+            if (kt + 1 < nk || more) sstore((gs + 1) & 1);
+            if (more) gload(kt + 2 - nk);
+            __syncthreads();
         }
         epilogue<EPI, BN, TM, TN, MB, NB>(g, acc, e_m0, e_n0, e_tile_n, wm, wn, l32, lh);
         if (!more) break;
@@ -337,10 +370,10 @@ static int cu_count() {
     return n;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
 void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
-    auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI>;
-    const size_t lds = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16);
+    auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI, BKT>;
+    const size_t lds = (size_t)2 * (BM + BN) * (BKT + 8) * sizeof(bf16);
     static bool attr_set = false;  // one context per process configures each instantiation once
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

@@ -208,7 +208,7 @@ mulo_status mulo_check_model_cfg(const mulo_model_cfg* c) {
     if ((int64_t)c->max_batch * c->max_block > (1 << 22)) return MULO_ERR_UNSUPPORTED;
     if (c->dtype == MULO_BF16) {
         if (c->head_dim != 64 && c->head_dim != 128) return MULO_ERR_UNSUPPORTED;
-        if ((c->d_model % 128) || (c->d_ffn % 64) || (c->max_seq % 8) || (c->max_block % 4))
+        if ((c->d_model % 128) || (c->d_ffn % 64) || c->d_ffn < 128 || (c->max_seq % 8) || (c->max_block % 4))
             return MULO_ERR_UNSUPPORTED;
     } else {
         if (c->max_seq + c->head_dim > 15000) return MULO_ERR_UNSUPPORTED;  // scores of a row live in LDS
