@@ -208,7 +208,7 @@ __device__ __forceinline__ f32x16 mma(const bf16x8& a, const bf16x8& b, const f3
 }
 
 // ---- BM x BN x 64 tiles, double-buffered LDS, one barrier per K-tile ---------------------------
-template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64, bool FULL = false>
 __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536) ? 1 : 2) void k_gemm_bf16(const GemmArgs g) {
     constexpr int BK = BKT, LDS_STRIDE = BKT + 8, CPR = BKT / 8;   // 16-byte chunks per tile row
     constexpr bool SWAP = EPI != EPI_V;
@@ -237,31 +237,53 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     const int chunk_len = total_tiles - chunk_base < chunk ? total_tiles - chunk_base : chunk;   // may be <= 0
     int tile = blockIdx.x / nxcd, tile_n = 0, m0 = 0, n0 = 0;
     const int kc8 = (tid % CPR) * 8, trow = tid / CPR;
-    const bf16* pa[LA];
-    const bf16* pb[LB];
+    // Operand addresses.  General case: one pointer per staged chunk.  FULL (M and N multiples of the
+    // tile, the launcher checks): the rows a lane fetches are a fixed stride apart, so a lane keeps
+    // ONE 32-bit offset (its row and chunk inside a 64-row pass) and the pass bases are wavefront-
+    // uniform scalars: global_load with a scalar base, 15 vector registers fewer.
+    constexpr int RP = NT / CPR;   // tile rows per pass
+    const bf16* pa[FULL ? 1 : LA];
+    const bf16* pb[FULL ? 1 : LB];
+    const char* sa[FULL ? LA : 1];
+    const char* sb[FULL ? LB : 1];
+    const uint32_t voff = (uint32_t)(trow * g.K + kc8) * 2u;
     auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
         const int t = chunk_base + local, grp = t / (tiles_m * GW), rem = t - grp * tiles_m * GW;
         const int gw = g.tiles_n - grp * GW < GW ? g.tiles_n - grp * GW : GW;
         tile_n = grp * GW + rem % gw;
         m0 = (rem / gw) * BM;
         n0 = tile_n * BN;
+        if constexpr (FULL) {
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            int r = m0 + trow + i * (NT / CPR);
-            r = r < g.M ? r : g.M - 1;
-            pa[i] = g.A + (int64_t)r * g.K + kc8;
+            for (int i = 0; i < LA; ++i) sa[i] = reinterpret_cast<const char*>(g.A + (int64_t)(m0 + i * RP) * g.K);
+#pragma unroll
+            for (int i = 0; i < LB; ++i) sb[i] = reinterpret_cast<const char*>(b_row<EPI, BN, TN>(g, n0, tile_n, i * RP));
+        } else {
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                int r = m0 + trow + i * RP;
+                r = r < g.M ? r : g.M - 1;
+                pa[i] = g.A + (int64_t)r * g.K + kc8;
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, trow + i * RP) + kc8;
         }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) pb[i] = b_row<EPI, BN, TN>(g, n0, tile_n, trow + i * (NT / CPR)) + kc8;
     };
 
     f32x16 acc[MB][NB];
     u32x4 ra[LA], rb[LB];
     auto gload = [&](int kt) {
+        if constexpr (FULL) {
 #pragma unroll
-        for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + kt * BK);
+            for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(sa[i] + kt * (BK * 2) + voff);
 #pragma unroll
-        for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(pb[i] + kt * BK);
+            for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(sb[i] + kt * (BK * 2) + voff);
+        } else {
+#pragma unroll
+            for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + kt * BK);
+#pragma unroll
+            for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(pb[i] + kt * BK);
+        }
     };
     const int nk = g.K / BK;
     auto sstore = [&](int buf) {
@@ -370,9 +392,9 @@ static int cu_count() {
     return n;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64>
+template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64, bool FULL = false>
 void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
-    auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI, BKT>;
+    auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI, BKT, FULL>;
     const size_t lds = (size_t)2 * (BM + BN) * (BKT + 8) * sizeof(bf16);
     static bool attr_set = false;  // one context per process configures each instantiation once
     if (!attr_set) {
@@ -389,8 +411,10 @@ void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
 template <int EPI>
 void dispatch(const GemmArgs& g, hipStream_t st) {
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
-    const bool big = g.M >= 1024 && (EPI == EPI_QK ? g.d % 256 == 0 : true);
-    if (big) run_gemm<256, 256, 4, 2, EPI>(g, (g.N + 255) / 256, 1, st);
+    // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
+    const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
+                      (int64_t)g.K * 256 * 2 < (1ll << 31);
+    if (big) run_gemm<256, 256, 4, 2, EPI, 64, true>(g, (g.N + 255) / 256, 1, st);
     else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, 2, st);
 }
 
