@@ -145,9 +145,10 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     sstore(0);
     __syncthreads();
     for (int t = 0; t < n_tiles; ++t) {
-        if (t + 1 < n_tiles) gload(t + 1);
         const int kv0 = t * BKV;
+        const int t_next = t + 1 < n_tiles ? t + 1 : t;   // the last tile is fetched twice: no branch in the body
         if (wave_live && kv0 <= a.P + wave_jmax) {
+            gload(t_next);
             const bf16* k = sK + (t & 1) * BKV * KS;
             const bf16* v = sV + (t & 1) * DH * VS;
             f32x16 s[2];
@@ -164,20 +165,22 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             // accumulator r of block kb holds key kv0 + kb*32 + 16*(r/8) + 8*lh + r%8 for query l32
             const bool need_mask = kv0 + BKV - 1 > a.P + wave_jmin;
             float mx = -__builtin_huge_valf();
+            if (need_mask) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+                        s[kb][r] = key <= qpos ? s[kb][r] : -__builtin_huge_valf();
+                    }
+            }
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = s[kb][r] * a.scale_log2;
-                    if (need_mask) {
-                        const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
-                        x = key <= qpos ? x : -__builtin_huge_valf();
-                    }
-                    s[kb][r] = x;
-                    mx = fmaxf(mx, x);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
+            // running maximum in exponent units (scores times log2(e) / sqrt(dh)); the scale is positive
+            const float m_new = fmaxf(m_run, mx * a.scale_log2);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             float ps = 0.f;
@@ -186,15 +189,18 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_new);
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], a.scale_log2, -m_new));
                     ps += p;
                     pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
                 }
             l_run = l_run * alpha + ps;
+            // the accumulators are rescaled only when some query of the wavefront raised its maximum
+            if (!__all(alpha == 1.0f)) {
 #pragma unroll
-            for (int i = 0; i < NDB; ++i)
+                for (int i = 0; i < NDB; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+                    for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+            }
             // O^T += V^T P^T : k-step ks covers keys kv0 + 16 ks .. +15
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -204,8 +210,11 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], o[i], 0, 0, 0);
                 }
             }
+            sstore((t + 1) & 1);
+        } else {
+            gload(t_next);
+            sstore((t + 1) & 1);
         }
-        if (t + 1 < n_tiles) sstore((t + 1) & 1);
         __syncthreads();
     }
 
