@@ -187,12 +187,16 @@ def main():
             e.update(bound="hbm", achieved=round(byts[name] / (avg * 1e-3) / 1e9, 1), unit="GB/s")
             e["frac"] = round(e["achieved"] / PEAK_HBM_GBS, 4)
         kernels[name] = e
+    # HBM bytes per launch of the roofline kernel: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB per dispatch, scale
+    # factors from the --calibrate-copy runs) of two rocprofv3 --pmc runs of this benchmark; a stored measurement,
+    # summarised in profiles/verify_step_cfg4_hbm_traffic.md (1325.0 MB fetched + 92.2 MB written)
+    measured_traffic = {"cfg4": 1.4172e9}
     roof = None
     if "gemm_gate_up" in kernels:
         k = kernels["gemm_gate_up"]
         roof = {"bound": "mfma", "kernel": "k_gemm_bf16<EPI_SWIGLU> (gate|up projection + SwiGLU)",
                 "achieved": k["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": k["frac"],
-                "traffic": None, "avg_ms": k["avg_ms"], "flops_per_launch": flops["gemm_gate_up"]}
+                "traffic": measured_traffic.get(c["name"]), "avg_ms": k["avg_ms"], "flops_per_launch": flops["gemm_gate_up"]}
     fwd_flops = nl * (flops["gemm_qkv"] + flops["gemm_out"] + flops["gemm_gate_up"] + flops["gemm_down"]
                       + flops["attention"]) + flops["gemm_lm_head"]
 
