@@ -42,6 +42,7 @@ struct GemmArgs {
     bf16* vc;             // V: V^T cache
     int d;                // QK: model width (segment size)
     int tiles_n;          // column tiles of the launch (set by the launcher)
+    int tile_n0;          // first column tile of the launch (set by the launcher)
     RopeArgs ra;
 };
 
@@ -57,7 +58,8 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
-__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+// g * sigmoid(g) with the hardware reciprocal (1 ulp; the product is rounded to bf16 right after)
+__device__ __forceinline__ float silu(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 // Source row of weight-tile row nl (fixed over the K loop) for each fused problem.
 template <int EPI, int BN, int TN>
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
         const int t = chunk_base + local, grp = t / (tiles_m * GW), rem = t - grp * tiles_m * GW;
         const int gw = g.tiles_n - grp * GW < GW ? g.tiles_n - grp * GW : GW;
-        tile_n = grp * GW + rem % gw;
+        tile_n = g.tile_n0 + grp * GW + rem % gw;
         m0 = (rem / gw) * BM;
         n0 = tile_n * BN;
         if constexpr (FULL) {
@@ -393,7 +395,7 @@ static int cu_count() {
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64, bool FULL = false>
-void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
+void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream_t st) {
     auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI, BKT, FULL>;
     const size_t lds = (size_t)2 * (BM + BN) * (BKT + 8) * sizeof(bf16);
     static bool attr_set = false;  // one context per process configures each instantiation once
@@ -405,6 +407,7 @@ void run_gemm(GemmArgs g, int tiles_n, int blocks_per_cu, hipStream_t st) {
     const int tiles_m = (g.M + BM - 1) / BM, total = tiles_m * tiles_n;
     const int resident = cu_count() * blocks_per_cu;
     g.tiles_n = tiles_n;
+    g.tile_n0 = tile_n0;
     hipLaunchKernelGGL(kern, dim3(total < resident ? total : resident), dim3(WGM * WGN * 64), lds, st, g);
 }
 
@@ -414,8 +417,19 @@ void dispatch(const GemmArgs& g, hipStream_t st) {
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
     const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
                       (int64_t)g.K * 256 * 2 < (1ll << 31);
-    if (big) run_gemm<256, 256, 4, 2, EPI, 64, true>(g, (g.N + 255) / 256, 1, st);
-    else run_gemm<128, 128, 2, 2, EPI>(g, (g.N + 127) / 128, 2, st);
+    if (big) {
+        // Whole rounds of 256x256 tiles, one tile per CU and round.  A last round that would leave more than
+        // half of the CUs idle is cut off and run as 128x256 tiles (twice as many workgroups, half the work each).
+        const int tiles_m = g.M / 256, tiles_n = g.N / 256, cus = cu_count();
+        const int total = tiles_m * tiles_n, rem = total % cus;
+        int n_main = tiles_n;
+        if (total > cus && rem > 0 && 2 * rem <= cus) n_main = (total - rem) / tiles_m;
+        if ((tiles_n - n_main) * tiles_m * 2 > cus) n_main = tiles_n;   // the cut-off part must fit one round
+        run_gemm<256, 256, 4, 2, EPI, 64, true>(g, 0, n_main, 1, st);
+        if (n_main < tiles_n) run_gemm<128, 256, 4, 2, EPI, 64, true>(g, n_main, tiles_n - n_main, 1, st);
+    } else {
+        run_gemm<128, 128, 2, 2, EPI>(g, 0, (g.N + 127) / 128, 2, st);
+    }
 }
 
 // ---------------------------------------------------------------- float32
