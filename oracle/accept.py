@@ -13,6 +13,12 @@ codebook entries of x~_i (Eq. 3); k = 1 gives Eq. 1.  With a uniform u in
 because u <= 1 - 2^-24, accepts every position when q and p hold the same
 bits.  The three quantities are float32 and the product is rounded to float32
 before the comparison (the precision the decision is taken in).
+
+Threshold form (Sec. 3.3, Eq. 5; the rule the paper itself runs): the draft
+token is kept iff its pooled target mass reaches a threshold,
+pbar_i >= tau, with no draft probability and no random number.  Eq. 5 writes
+">=" and the listing of Alg. 1 writes ">"; the equation is taken (the two
+differ only when pbar equals tau bit for bit).  pbar and tau are float32.
 """
 import numpy as np
 
@@ -55,3 +61,13 @@ def near_tie(pbar, q_tok, u, width=NEAR_TIE):
     q_tok = np.asarray(q_tok, dtype=np.float64)
     u = np.asarray(u, dtype=np.float64)
     return np.abs(pbar - u * q_tok) < width * q_tok
+
+
+def accept_test_tau(pbar, tau):
+    """accept iff pbar >= tau, both float32 (Eq. 5)."""
+    return np.asarray(pbar, dtype=np.float32) >= np.float32(tau)
+
+
+def near_tie_tau(pbar, tau, width=NEAR_TIE):
+    """|pbar - tau| < width * tau: decisions that a last-ulp difference in pbar could flip."""
+    return np.abs(np.asarray(pbar, dtype=np.float64) - float(np.float32(tau))) < width * float(np.float32(tau))

@@ -16,6 +16,9 @@ mode 0 (default): every marked position draws from the residual.
 mode 1: positions that were themselves rejected draw from the residual, the
         neighbours marked only by expansion draw from p_u (the paper re-samples
         expanded positions from the target model, Sec. 3.3 after Eq. 7).
+mode 2: every marked position draws from p_u: the paper's own Step 6 (Alg. 1),
+        which samples rejected tokens from the target model; no draft
+        distribution is needed.
 """
 import numpy as np
 
@@ -74,7 +77,7 @@ def resample_block(p, q_rows, q_row_index, draft_tokens, mask, accept, words, mo
     for u in range(L):
         if not mask[u]:
             continue
-        if mode == 1 and accept[u]:
+        if mode == 2 or (mode == 1 and accept[u]):
             Wi = integer_weights(p[u])
         else:
             Wi = residual_weights(p[u], q_rows[q_row_index[u]])

@@ -12,8 +12,11 @@ from . import upsample as UP
 
 
 def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1,
-           seed=0, rng_counter=0, nbr=None, mode=0):
-    """Decision stage on given logits (Sec. 3.1 Eq. 1-3, Sec. 3.3 Eq. 6-7).
+           seed=0, rng_counter=0, nbr=None, mode=0, accept_mode=0, tau=0.0):
+    """Decision stage on given logits (Sec. 3.1 Eq. 1-3, Sec. 3.3 Eq. 5-7).
+
+    accept_mode 0: speculative test u q < pbar (Eq. 1 / Eq. 3); accept_mode 1:
+    threshold test pbar >= tau (Eq. 5), where q_rows may be None if mode == 2.
 
     logits: float [B, L, V]; q_rows: float32 [B, n_q, V]; q_row_index: int [L]
     or None (identity); draft_tokens: int [B, L].
@@ -34,12 +37,16 @@ def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1
     for b in range(B):
         p = A.target_probs(logits[b])                                   # Step 3 -> p_i
         pbar = A.pooled_mass(p, toks[b], nbr)                           # Eq. 3 numerator
-        q_tok = np.asarray(q_rows[b], dtype=np.float32)[qi, toks[b]]    # q_i(x~_i)
-        acc = A.accept_test(pbar, q_tok, u[b])                          # Eq. 1
+        qb = None if q_rows is None else np.asarray(q_rows[b], dtype=np.float32)
+        q_tok = np.zeros(L, np.float32) if qb is None else qb[qi, toks[b]]   # q_i(x~_i)
+        if accept_mode == 1:
+            acc = A.accept_test_tau(pbar, tau)                          # Eq. 5
+            nt = A.near_tie_tau(pbar, tau)
+        else:
+            acc = A.accept_test(pbar, q_tok, u[b])                      # Eq. 1
+            nt = A.near_tie(pbar, q_tok, u[b])
         mask, t0 = LOC.local_mask(acc, W, n0, radius, expand)           # Eq. 6-7
-        tok_out = RS.resample_block(p, np.asarray(q_rows[b], dtype=np.float32), qi,
-                                    toks[b], mask, acc, words[b], mode)  # Eq. 2
-        nt = A.near_tie(pbar, q_tok, u[b])
+        tok_out = RS.resample_block(p, qb, qi, toks[b], mask, acc, words[b], mode)  # Eq. 2 / Step 6
         out["p"][b], out["pbar"][b], out["q_tok"][b] = p, pbar, q_tok
         out["accept"][b], out["near_tie"][b] = acc, nt
         out["mask"][b], out["t0"][b], out["tokens_out"][b] = mask, t0, tok_out
@@ -49,7 +56,7 @@ def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1
 
 def verify_step(decoder, P, draft_lo, draft_tokens_lo, prev_tokens, *, h_blk, w, r, W, n0,
                 radius, expand=1, seed=0, rng_counter=0, nbr=None, mode=0,
-                input_is_probs=False):
+                input_is_probs=False, accept_mode=0, tau=0.0):
     """Steps 2-5 + resampling for one block of L = (r*h_blk)*(r*w) positions.
 
     decoder: oracle.decoder.DecoderOracle whose cache holds P valid rows;
@@ -65,6 +72,6 @@ def verify_step(decoder, P, draft_lo, draft_tokens_lo, prev_tokens, *, h_blk, w,
                           tokens_hi[:, :L - 1]], axis=1)
     logits = decoder.forward(inp, P).numpy()
     out = decide(logits, q_lo, q_row, tokens_hi, W=W, n0=n0, radius=radius, expand=expand,
-                 seed=seed, rng_counter=rng_counter, nbr=nbr, mode=mode)
+                 seed=seed, rng_counter=rng_counter, nbr=nbr, mode=mode, accept_mode=accept_mode, tau=tau)
     out.update(tokens_hi=tokens_hi, q_lo=q_lo, q_row=q_row, logits=logits)
     return out

@@ -426,3 +426,90 @@ def test_acceptance_rate_closed_form_large_vocab():
         tv = 0.5 * np.abs(out["p"][0].astype(np.float64) - q[0]).sum(-1).mean()
         assert abs((1 - tv) - want) < 0.03
         assert abs(out["accept"].mean() - (1 - tv)) < 4 * np.sqrt(0.25 / n)
+
+
+# ------------------------------------------------------------------ threshold rule (Eq. 5)
+def test_tau_rule_hand_example_and_the_tie_is_accepted():
+    # two-entry codebook, logits (0, ln 3): p = (1/4, 3/4) exactly representable
+    z = np.array([[[0.0, np.log(3.0)], [0.0, np.log(3.0)], [0.0, 0.0], [0.0, 0.0]]], np.float32)
+    toks = np.array([[0, 1, 0, 1]])
+    out = ST.decide(z, None, None, toks, W=4, n0=0, radius=0, accept_mode=1, tau=0.3, mode=2)
+    assert np.allclose(out["pbar"][0], [0.25, 0.75, 0.5, 0.5], atol=1e-7)
+    assert out["accept"][0].tolist() == [0, 1, 1, 1]
+    # Eq. 5 reads ">=": a pooled mass of exactly tau is accepted (a ">" would reject rows 2 and 3)
+    out = ST.decide(z, None, None, toks, W=4, n0=0, radius=0, accept_mode=1, tau=0.5, mode=2)
+    assert out["pbar"][0, 2] == np.float32(0.5) and out["accept"][0].tolist() == [0, 1, 1, 1]
+    # pooling over both entries (k = V): mass 1 everywhere, everything accepted at any tau <= 1
+    nbr = np.array([[0, 1], [1, 0]])
+    out = ST.decide(z, None, None, toks, W=4, n0=0, radius=0, accept_mode=1, tau=0.99, mode=2, nbr=nbr)
+    assert out["accept"].all() and (out["tokens_out"] == toks).all() and (out["t0"] == 4).all()
+
+
+def test_tau_rule_limits_monotone_and_deterministic():
+    rng = np.random.default_rng(21)
+    B, H, W, V = 2, 6, 6, 96
+    L = H * W
+    z = rng.normal(0, 2.0, (B, L, V)).astype(np.float32)
+    toks = rng.integers(0, V, (B, L))
+    kw = dict(W=W, n0=0, radius=1, accept_mode=1, mode=2, seed=3)
+    assert ST.decide(z, None, None, toks, tau=0.0, **kw)["accept"].all()          # pbar >= 0 always
+    assert not ST.decide(z, None, None, toks, tau=1.5, **kw)["accept"].any()      # a probability never reaches 1.5
+    prev = None
+    for tau in (1e-4, 1e-3, 1e-2, 1e-1, 0.5):
+        acc = ST.decide(z, None, None, toks, tau=tau, **kw)["accept"].astype(bool)
+        if prev is not None:
+            assert not (acc & ~prev).any()      # raising tau only removes accepted positions
+        prev = acc
+    # accepted set = {pbar >= tau} for the float64 softmax evaluated independently (scipy)
+    p_ref = scipy.special.softmax(z.astype(np.float64), axis=-1)
+    pt = np.take_along_axis(p_ref, toks[..., None], -1)[..., 0]
+    out = ST.decide(z, None, None, toks, tau=1e-2, **kw)
+    clear = np.abs(pt - 1e-2) > 1e-6
+    assert np.array_equal(out["accept"].astype(bool)[clear], (pt >= 1e-2)[clear])
+    # no random number enters the accept decision: it does not move with the counter ...
+    a = ST.decide(z, None, None, toks, tau=1e-2, rng_counter=1, **kw)
+    b = ST.decide(z, None, None, toks, tau=1e-2, rng_counter=2, **kw)
+    assert np.array_equal(a["accept"], b["accept"]) and np.array_equal(a["mask"], b["mask"])
+    # ... while the re-drawn tokens do
+    assert not np.array_equal(a["tokens_out"], b["tokens_out"])
+
+
+def test_tau_rule_marked_positions_are_drawn_from_the_target_distribution():
+    # Step 6 of Alg. 1: a marked position gets a sample of p (mode 2), by the integer inverse CDF
+    rng = np.random.default_rng(5)
+    V, L = 40, 64
+    z = rng.normal(0, 1.5, (1, L, V)).astype(np.float32)
+    toks = rng.integers(0, V, (1, L))
+    out = ST.decide(z, None, None, toks, W=8, n0=0, radius=0, accept_mode=1, tau=0.01, mode=2, seed=11, rng_counter=7)
+    mask = out["mask"][0].astype(bool)
+    assert mask.any() and not mask.all()
+    for u_ in np.flatnonzero(mask):
+        Wi = RS.integer_weights(out["p"][0, u_])
+        assert out["tokens_out"][0, u_] == RS.draw(Wi, out["words"][0, u_])
+    assert np.array_equal(out["tokens_out"][0][~mask], toks[0][~mask])
+    # law of the draw: over many words the frequencies follow p (chi-square against p itself)
+    p = out["p"][0, 0].astype(np.float64)
+    Wi = RS.integer_weights(out["p"][0, 0])
+    words = PH.step_words(123, 0, PH.STREAM_SAMPLE, 1, 20000)[0]
+    cnt = np.bincount([RS.draw(Wi, w) for w in words], minlength=V)
+    keep = p * len(words) > 5
+    chi = ((cnt[keep] - p[keep] * len(words)) ** 2 / (p[keep] * len(words))).sum()
+    assert chi < scipy.stats.chi2.ppf(0.9999, keep.sum() - 1)
+
+
+def test_tau_rule_pooled_mass_with_neighbour_table():
+    # pooled mass over k neighbours is the plain sum of those probabilities (Eq. 5 with B_k)
+    rng = np.random.default_rng(8)
+    V, L, k = 32, 16, 5
+    z = rng.normal(0, 1.0, (1, L, V)).astype(np.float32)
+    toks = rng.integers(0, V, (1, L))
+    nbr = np.stack([np.concatenate([[x], rng.choice(np.delete(np.arange(V), x), k - 1, replace=False)]) for x in range(V)])
+    out = ST.decide(z, None, None, toks, W=4, n0=0, radius=1, accept_mode=1, tau=0.2, mode=2, nbr=nbr)
+    p_ref = scipy.special.softmax(z[0].astype(np.float64), axis=-1)
+    for t in range(L):
+        want = sum(p_ref[t, x] for x in nbr[toks[0, t]])
+        assert abs(out["pbar"][0, t] - want) < 1e-6
+        if abs(want - 0.2) > 1e-5:
+            assert bool(out["accept"][0, t]) == (want >= 0.2)
+    one = ST.decide(z, None, None, toks, W=4, n0=0, radius=1, accept_mode=1, tau=0.2, mode=2)
+    assert (out["accept"] >= one["accept"]).all()      # pooling can only add mass
