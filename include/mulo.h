@@ -91,6 +91,8 @@ typedef struct {
     void *k, *v;
 } mulo_kv;
 
+typedef enum { MULO_ACCEPT_RATIO = 0, MULO_ACCEPT_TAU = 1 } mulo_accept_mode;
+
 /* Parameters of the decision stage (host struct).
  *   H, W        target grid; n0 first position of the block; L block length
  *   radius      l of Eq. 6 (>= 0); -1 selects the raster-scan rule of standard
@@ -102,7 +104,13 @@ typedef struct {
  *               NULL) is the plain test of Eq. 1
  *   resample_mode 0: every marked position draws from the residual of Eq. 2;
  *               1: rejected positions draw from the residual, positions marked
- *               only by expansion draw from p
+ *               only by expansion draw from p; 2: every marked position draws
+ *               from p (Alg. 1 Step 6 samples rejected tokens from the target)
+ *   accept_mode MULO_ACCEPT_RATIO: speculative test u q < pbar (Eq. 1 / Eq. 3);
+ *               MULO_ACCEPT_TAU: the threshold rule of Eq. 5, accept iff
+ *               pbar >= tau (float32), no draft probability and no uniform;
+ *               with resample_mode 2 the draft distribution is not read at all
+ *   tau         threshold of Eq. 5, finite and >= 0 (read in MULO_ACCEPT_TAU only)
  *   seed, rng_counter  Philox4x32-10 key and per-step counter; position t of
  *               batch element b uses counter words (t, b, counter_lo,
  *               stream << 24 | counter_hi & 0xffffff), stream 0 for the accept
@@ -114,6 +122,8 @@ typedef struct {
     const int32_t *nbr;
     int32_t resample_mode;
     uint64_t seed, rng_counter;
+    int32_t accept_mode;
+    float tau;
 } mulo_step_params;
 
 /* Static description of a status code; never NULL. */
@@ -163,17 +173,18 @@ MULO_API mulo_status mulo_upsample_draft(mulo_ctx *ctx, int32_t B, int32_t h, in
 MULO_API mulo_status mulo_verify_forward(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int32_t L, int32_t P,
                                 const int32_t *in_tokens, const void *in_embeds, float *logits);
 
-/* Steps 4-5 and the residual re-draw (Sec. 3.1 Eq. 1-3; Sec. 3.3 Eq. 6-7).
+/* Steps 4-5 and the re-draw of the marked positions (Sec. 3.1 Eq. 1-3; Sec. 3.3 Eq. 5-7).
  *   logits       device float32 [B, L, vocab]  target logits of the block
  *   q            device float32 draft probabilities; row of position t of batch
  *                b starts at q + b * q_batch_stride + row(t) * vocab, where
- *                row(t) = q_row[t], or t when q_row is NULL
+ *                row(t) = q_row[t], or t when q_row is NULL; may be NULL when
+ *                accept_mode is MULO_ACCEPT_TAU and resample_mode is 2
  *   draft_tokens device int32 [B, L]  x~ on the target grid
  *   tokens_out   device int32 [B, L]  (out) x~ where unmarked, re-drawn where marked
  *   accept, mask device uint8 [B, L]  (out) 1 = accepted / 1 = marked (R_X)
  *   t0           device int32 [B]     (out) first rejected position, L if none
  *   stats        device int32 [B, 4]  (out) accepted, rejected, marked, near ties
- *                (|pbar - u q| < 1e-4 q)
+ *                (|pbar - u q| < 1e-4 q; threshold rule: |pbar - tau| < 1e-4 tau)
  *   p_probs      device float32 [B, L, vocab] (out) or NULL: softmax(logits) */
 MULO_API mulo_status mulo_accept_local_resample(mulo_ctx *ctx, int32_t B, const mulo_step_params *p,
                                        const float *logits, const float *q, const int32_t *q_row,
@@ -186,7 +197,8 @@ MULO_API mulo_status mulo_accept_local_resample(mulo_ctx *ctx, int32_t B, const 
  * [prev, x~_0 .. x~_{L-2}] so that logit row j is p for draft position j, then
  * decide and re-draw.  Cache rows [P, P+L) are written; rows after the first
  * rejection are stale afterwards and P is never advanced (the caller commits).
- *   draft        device float32 [B, h_blk*w, vocab] logits (or probabilities)
+ *   draft        device float32 [B, h_blk*w, vocab] logits (or probabilities); may be
+ *                NULL when accept_mode is MULO_ACCEPT_TAU and resample_mode is 2
  *   draft_tokens device int32 [B, h_blk*w]
  *   prev_tokens  device int32 [B]  last committed (or last prefix) token
  *   tokens_hi    device int32 [B, L] (out) or NULL: the up-sampled draft x~

@@ -44,7 +44,8 @@ class StepParams(C.Structure):
     _fields_ = [("H", C.c_int32), ("W", C.c_int32), ("n0", C.c_int32), ("L", C.c_int32),
                 ("radius", C.c_int32), ("expand", C.c_int32), ("pool_k", C.c_int32),
                 ("nbr", C.c_void_p), ("resample_mode", C.c_int32),
-                ("seed", C.c_uint64), ("rng_counter", C.c_uint64)]
+                ("seed", C.c_uint64), ("rng_counter", C.c_uint64),
+                ("accept_mode", C.c_int32), ("tau", C.c_float)]
 
 
 _lib = None
@@ -110,9 +111,13 @@ def make_cfg(model, max_batch, max_seq, max_block):
                     MULO_BF16 if model["dtype"] == "bf16" else MULO_F32, model.get("rms_eps", 1e-5))
 
 
-def make_params(H, W, n0, L, radius, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0, rng_counter=0):
+MULO_ACCEPT_RATIO, MULO_ACCEPT_TAU = 0, 1
+
+
+def make_params(H, W, n0, L, radius, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0, rng_counter=0,
+                accept_mode=MULO_ACCEPT_RATIO, tau=0.0):
     return StepParams(H, W, n0, L, radius, expand, pool_k, _ptr(nbr, torch.int32, True), resample_mode,
-                      seed, rng_counter)
+                      seed, rng_counter, accept_mode, tau)
 
 
 class Ctx:
@@ -175,7 +180,7 @@ def mulo_accept_local_resample(ctx, B, params, logits, q, q_row, q_batch_stride,
                                accept, mask, t0, stats, p_probs=None):
     f32, i32, u8 = torch.float32, torch.int32, torch.uint8
     _check(load_library().mulo_accept_local_resample(
-        ctx.handle, B, C.byref(params), _ptr(logits, f32), _ptr(q, f32), _ptr(q_row, i32, True),
+        ctx.handle, B, C.byref(params), _ptr(logits, f32), _ptr(q, f32, True), _ptr(q_row, i32, True),
         int(q_batch_stride), _ptr(draft_tokens, i32), _ptr(tokens_out, i32), _ptr(accept, u8), _ptr(mask, u8),
         _ptr(t0, i32), _ptr(stats, i32), _ptr(p_probs, f32, True)), "mulo_accept_local_resample")
 
@@ -185,7 +190,7 @@ def mulo_verify_step(ctx, kv, B, P, params, h_blk, w, r, draft, input_is_probs, 
     f32, i32, u8 = torch.float32, torch.int32, torch.uint8
     kvs = KV(_ptr(kv[0], ctx.tdtype), _ptr(kv[1], ctx.tdtype))
     _check(load_library().mulo_verify_step(
-        ctx.handle, C.byref(kvs), B, P, C.byref(params), h_blk, w, r, _ptr(draft, f32), int(input_is_probs),
+        ctx.handle, C.byref(kvs), B, P, C.byref(params), h_blk, w, r, _ptr(draft, f32, True), int(input_is_probs),
         _ptr(draft_tokens, i32), _ptr(prev_tokens, i32), _ptr(tokens_out, i32), _ptr(accept, u8),
         _ptr(mask, u8), _ptr(t0, i32), _ptr(stats, i32), _ptr(tokens_hi, i32, True), _ptr(logits, f32, True)),
         "mulo_verify_step")

@@ -231,8 +231,10 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
     const int tok = clamp_tok(a.draft_tokens[row], a.V);
     float ztok = 0.f, qt = 0.f;
     if (tid == 0) {
-        const int qr = a.q_row ? a.q_row[t] : t;
-        qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
+        if (a.accept_mode == 0) {
+            const int qr = a.q_row ? a.q_row[t] : t;
+            qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
+        }
         ztok = z[tok];
     }
     RowRegs<NV4> rr;
@@ -252,14 +254,17 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
     if (tid == 0) {
         const uint32_t w0 = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24, a.key0, a.key1);
         const float u = (float)(w0 >> 8) * 5.9604644775390625e-08f;  // 2^-24, exact
-        const float uq = __fmul_rn(u, qt);
-        const bool ok = uq < pbar;  // Eq. 1 without the division: u q < pbar
+        // Eq. 1 without the division: u q < pbar; threshold rule (Eq. 5): pbar >= tau, written as
+        // "tau' < pbar or equal" through the same comparison with uq := tau
+        const bool tau_rule = a.accept_mode == 1;
+        const float uq = tau_rule ? a.tau : __fmul_rn(u, qt);
+        const bool ok = tau_rule ? pbar >= uq : uq < pbar;
         a.accept[row] = ok ? 1 : 0;
         a.rowmax[row] = m;
         a.rowinv[row] = inv;
         atomicAdd(&a.stats[b * 4 + (ok ? 0 : 1)], 1);
         if (!ok) atomicMin(&a.t0[b], t);
-        if (fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, qt)) atomicAdd(&a.stats[b * 4 + 3], 1);
+        if (fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, tau_rule ? a.tau : qt)) atomicAdd(&a.stats[b * 4 + 3], 1);
     }
 }
 
@@ -314,9 +319,10 @@ __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
     const int V = a.V, nv4 = V >> 2, nchunks = (nv4 + 63) >> 6;
     const float4* z4 = reinterpret_cast<const float4*>(a.logits + row * V);
     const int qr = a.q_row ? a.q_row[t] : t;
-    const float4* q4 = reinterpret_cast<const float4*>(a.q + b * a.q_batch_stride + (int64_t)qr * V);
+    bool use_p = a.resample_mode == 2 || ((a.resample_mode == 1) && a.accept[row] != 0);
+    // the draft row is read only for residual weights (it may be absent when every draw is from p)
+    const float4* q4 = a.q ? reinterpret_cast<const float4*>(a.q + b * a.q_batch_stride + (int64_t)qr * V) : z4;
     const float m = a.rowmax[row], inv = a.rowinv[row];
-    bool use_p = (a.resample_mode == 1) && a.accept[row] != 0;
     const uint32_t word = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24 | (1u << 24),
                                        a.key0, a.key1);
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);

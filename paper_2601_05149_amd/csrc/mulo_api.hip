@@ -153,8 +153,10 @@ void enqueue_upsample(mulo_ctx* c, int B, int h, int w, int r, const float* draf
     PROF(MULO_PROF_UPSAMPLE);
     const int V = c->cfg.vocab;
     const int64_t rows = (int64_t)B * h * w;
-    if (input_is_probs) launch_copy_rows(draft, q_lo, rows * V, c->st);
-    else launch_softmax_rows(draft, q_lo, rows, V, c->st);
+    if (draft) {   // the threshold rule with target re-draws needs no draft distribution
+        if (input_is_probs) launch_copy_rows(draft, q_lo, rows * V, c->st);
+        else launch_softmax_rows(draft, q_lo, rows, V, c->st);
+    }
     launch_upsample_tokens(draft_tokens, tokens_hi, q_row, B, h, w, r, c->st);
     if (q_hi) launch_gather_rows(q_lo, q_row, q_hi, B, h * w, h * r * w * r, V, c->st);
 }
@@ -171,6 +173,8 @@ void fill_decide(DecideArgs& a, const mulo_ctx* ctx, int B, const mulo_step_para
     a.pool_k = p->pool_k < 1 ? 1 : p->pool_k;
     a.nbr = p->nbr;
     a.resample_mode = p->resample_mode;
+    a.accept_mode = p->accept_mode;
+    a.tau = p->tau;
     a.key0 = (uint32_t)(p->seed & 0xFFFFFFFFu);
     a.key1 = (uint32_t)(p->seed >> 32);
     a.ctr_lo = (uint32_t)(p->rng_counter & 0xFFFFFFFFu);
@@ -219,7 +223,9 @@ mulo_status mulo_check_model_cfg(const mulo_model_cfg* c) {
 mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mulo_step_params* p) {
     if (!c || !p) return MULO_ERR_NULL;
     if (B < 1 || p->H < 1 || p->W < 1 || p->L < 1 || p->n0 < 0 || p->radius < -1 || p->expand < 0 ||
-        p->pool_k < 1 || p->resample_mode < 0 || p->resample_mode > 1)
+        p->pool_k < 1 || p->resample_mode < 0 || p->resample_mode > 2 ||
+        (p->accept_mode != MULO_ACCEPT_RATIO && p->accept_mode != MULO_ACCEPT_TAU) ||
+        (p->accept_mode == MULO_ACCEPT_TAU && !(p->tau >= 0.f && p->tau <= 3.0e38f)))
         return MULO_ERR_RANGE;
     if ((int64_t)p->radius * p->expand > 4096) return MULO_ERR_RANGE;
     if (B > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
@@ -331,10 +337,11 @@ mulo_status mulo_accept_local_resample(mulo_ctx* ctx, int32_t B, const mulo_step
                                        const float* q, const int32_t* q_row, int64_t q_batch_stride,
                                        const int32_t* draft_tokens, int32_t* tokens_out, uint8_t* accept,
                                        uint8_t* mask, int32_t* t0, int32_t* stats, float* p_probs) {
-    if (!ctx || !p || !logits || !q || !draft_tokens || !tokens_out || !accept || !mask || !t0 || !stats)
+    if (!ctx || !p || !logits || !draft_tokens || !tokens_out || !accept || !mask || !t0 || !stats)
         return MULO_ERR_NULL;
     const mulo_status s = mulo_check_step_params(&ctx->cfg, B, p);
     if (s != MULO_OK) return s;
+    if (!q && !(p->accept_mode == MULO_ACCEPT_TAU && p->resample_mode == 2)) return MULO_ERR_NULL;
     if (q_batch_stride < 0) return MULO_ERR_RANGE;
     DecideArgs a{};
     fill_decide(a, ctx, B, p);
@@ -350,11 +357,12 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
                              const int32_t* draft_tokens, const int32_t* prev_tokens, int32_t* tokens_out,
                              uint8_t* accept, uint8_t* mask, int32_t* t0, int32_t* stats, int32_t* tokens_hi,
                              float* logits) {
-    if (!ctx || !p || !draft || !draft_tokens || !prev_tokens || !tokens_out || !accept || !mask || !t0 ||
-        !stats)
+    if (!ctx || !p || !draft_tokens || !prev_tokens || !tokens_out || !accept || !mask || !t0 || !stats)
         return MULO_ERR_NULL;
     mulo_status s = mulo_check_step_params(&ctx->cfg, B, p);
     if (s != MULO_OK) return s;
+    const bool need_q = !(p->accept_mode == MULO_ACCEPT_TAU && p->resample_mode == 2);
+    if (need_q && !draft) return MULO_ERR_NULL;
     if (h_blk < 1 || w < 1 || r < 1) return MULO_ERR_RANGE;
     if ((int64_t)h_blk * r * w * r != p->L || w * r != p->W) return MULO_ERR_SHAPE;
     s = check_forward_args(ctx, kv, B, p->L, P);
@@ -365,14 +373,15 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     int32_t* thi = tokens_hi ? tokens_hi : ctx->tokens_hi;
     float* lg = logits ? logits : ctx->logits;
     // Step 2
-    enqueue_upsample(ctx, B, h_blk, w, r, draft, input_is_probs, draft_tokens, thi, ctx->q_lo, ctx->q_row, nullptr);
+    enqueue_upsample(ctx, B, h_blk, w, r, need_q ? draft : nullptr, input_is_probs, draft_tokens, thi, ctx->q_lo,
+                     ctx->q_row, nullptr);
     // Step 3: inputs [prev, x~_0 .. x~_{L-2}] so that logit row j is p of draft position j
     { mulo_ctx* c = ctx; PROF(MULO_PROF_OTHER); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st); }
     enqueue_forward(ctx, kv, B, L, P, ctx->inputs, nullptr, lg);
     // Steps 4-5 + residual re-draw
     DecideArgs a{};
     fill_decide(a, ctx, B, p);
-    a.logits = lg; a.q = ctx->q_lo; a.q_row = ctx->q_row; a.q_batch_stride = (int64_t)n_lo * V;
+    a.logits = lg; a.q = need_q ? ctx->q_lo : nullptr; a.q_row = ctx->q_row; a.q_batch_stride = (int64_t)n_lo * V;
     a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = nullptr;
     enqueue_decide(ctx, a);

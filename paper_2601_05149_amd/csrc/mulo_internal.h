@@ -14,7 +14,9 @@ struct DecideArgs {
     int rho;          // Chebyshev radius expand*radius; -1 = raster-scan rule
     int pool_k;
     const int32_t* nbr;
-    int resample_mode;
+    int resample_mode;   // 0 residual, 1 residual for rejected / p for expanded, 2 p
+    int accept_mode;     // 0: u q < pbar (Eq. 1 / 3), 1: pbar >= tau (Eq. 5)
+    float tau;
     uint32_t key0, key1, ctr_lo, ctr_hi24;
     const float* logits;        // [B, L, V]
     const float* q;             // rows of V floats

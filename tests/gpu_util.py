@@ -96,7 +96,7 @@ def compare_decisions(gpu, ref, draft_tokens, q_rows, q_row_index, mode=0, label
         for u in bad:
             assert ref["mask"][b, u], "%s: unmarked position changed" % label
             qi = u if q_row_index is None else int(q_row_index[u])
-            if mode == 1 and acc_r[b, u]:
+            if mode == 2 or (mode == 1 and acc_r[b, u]):
                 Wi = RS.integer_weights(ref["p"][b, u])
             else:
                 Wi = RS.residual_weights(ref["p"][b, u], q_rows[b][qi])

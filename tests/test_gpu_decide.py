@@ -48,9 +48,10 @@ def run_decide(ctx, zp, q, toks, q_row=None, p_probs=False, **pk):
     params = mulo.make_params(nbr=nbr_d, pool_k=1 if nbr is None else nbr.shape[1], **pk)
     out = decide_buffers(B, L)
     pp = torch.empty(B, L, V, device=DEV) if p_probs else None
-    mulo.mulo_accept_local_resample(ctx, B, params, dev(zp, torch.float32), dev(q, torch.float32),
+    mulo.mulo_accept_local_resample(ctx, B, params, dev(zp, torch.float32),
+                                    None if q is None else dev(q, torch.float32),
                                     None if q_row is None else dev(q_row, torch.int32),
-                                    q.shape[1] * V, dev(toks, torch.int32), out["tokens_out"],
+                                    0 if q is None else q.shape[1] * V, dev(toks, torch.int32), out["tokens_out"],
                                     out["accept"], out["mask"], out["t0"], out["stats"], pp)
     torch.cuda.synchronize()
     res = to_np(out)
@@ -216,3 +217,53 @@ def test_decide_full_size(name, B, L, radius):
     rep = compare_decisions(got, ref, toks, q, None, label=name)
     say("  %s: acc %.3f marked %.3f %r" % (name, ref["accept"].mean(), ref["mask"].mean(), rep))
     assert rep["sequences_checked"] >= B - 2
+
+
+# --------------------------------------------------------------- threshold rule (Eq. 5)
+TAU_CASES = [
+    # B, H, W, n0, L, V, tau, radius, mode, pool_k, with_q
+    (2, 16, 16, 0, 256, 1024, 1e-3, 1, 2, 1, False),       # the paper's rule: no draft distribution at all
+    (4, 32, 32, 512, 256, 8192, 1e-4, 1, 2, 1, False),
+    (1, 48, 48, 1728, 576, 16384, 3e-3, 2, 2, 16, False),  # pooled over 16 codebook neighbours
+    (2, 10, 10, 20, 60, 1000, 5e-3, 1, 0, 8, True),        # threshold accept, residual re-draw (needs q)
+    (1, 8, 8, 0, 64, 20000, 1e-4, 1, 2, 1, False),         # vocabulary beyond the register-resident path
+]
+
+
+@pytest.mark.parametrize("case", TAU_CASES, ids=lambda c: "B%d_%dx%d_n%d_L%d_V%d_tau%g_r%d_m%d_k%d_q%d" % c)
+def test_tau_rule_parity(case):
+    B, H, W, n0, L, V, tau, radius, mode, k, with_q = case
+    say("tau-rule case %r" % (case,))
+    ctx = decide_ctx(V, 4, 1024)
+    zp, q, toks = clean_inputs(B, L, V, 1.0, seed=5)
+    nbr = G.neighbour_table(V, k, seed=5) if k > 1 else None
+    kw = dict(W=W, n0=n0, radius=radius, expand=1, seed=31, rng_counter=(2 << 32) | 4)
+    ref = ST.decide(zp, q if with_q else None, None, toks, nbr=nbr, mode=mode, accept_mode=1, tau=tau, **kw)
+    got = run_decide(ctx, zp, q if with_q else None, toks, p_probs=True, H=H, L=L, nbr=nbr, resample_mode=mode,
+                     accept_mode=mulo.MULO_ACCEPT_TAU, tau=tau, **kw)
+    rep = compare_decisions(got, ref, toks, q, None, mode=mode, label=str(case))
+    say("  acc rate %.3f marked %.3f | %r" % (ref["accept"].mean(), ref["mask"].mean(), rep))
+    assert 0.02 < ref["accept"].mean() < 0.999          # the case exercises both outcomes
+    assert np.abs(got["p"] - ref["p"]).max() <= 1e-5
+    assert rep["sequences_checked"] >= 1
+    # no random number enters the accept decision: another counter gives the same flags and mask
+    kw2 = dict(kw, rng_counter=99)
+    got2 = run_decide(ctx, zp, q if with_q else None, toks, H=H, L=L, nbr=nbr, resample_mode=mode,
+                      accept_mode=mulo.MULO_ACCEPT_TAU, tau=tau, **kw2)
+    assert np.array_equal(got2["accept"], got["accept"]) and np.array_equal(got2["mask"], got["mask"])
+
+
+def test_tau_rule_limits_and_errors_on_device():
+    B, H, W, L, V = 2, 8, 8, 64, 512
+    ctx = decide_ctx(V, 4, 1024)
+    zp, q, toks = clean_inputs(B, L, V, 1.0, seed=6)
+    kw = dict(H=H, W=W, n0=0, L=L, radius=1, resample_mode=2, accept_mode=mulo.MULO_ACCEPT_TAU)
+    allacc = run_decide(ctx, zp, None, toks, tau=0.0, **kw)
+    assert allacc["accept"].all() and not allacc["mask"].any() and np.array_equal(allacc["tokens_out"], toks)
+    none = run_decide(ctx, zp, None, toks, tau=1.5, **kw)
+    assert not none["accept"].any() and none["mask"].all() and (none["t0"] == 0).all()
+    # a missing draft distribution is an error wherever it would be read
+    for bad in (dict(kw, resample_mode=0), dict(kw, accept_mode=mulo.MULO_ACCEPT_RATIO)):
+        with pytest.raises(mulo.MuloError) as e:
+            run_decide(ctx, zp, None, toks, tau=1e-3, **bad)
+        assert e.value.status == 1

@@ -191,3 +191,56 @@ def test_step_argument_errors():
                               out["mask"], out["t0"], out["stats"])
     assert e.value.status == 2
     assert (out["tokens_out"] == -7).all()          # nothing was written
+
+
+def test_step_tau_rule_without_draft_distribution_vs_oracle():
+    """The paper's own rule through the whole step (Eq. 5 + Alg. 1 Step 6 as a one-shot re-draw from p):
+    no draft logits are passed, only the draft tokens."""
+    c = WC.get("cfg1")
+    m, B, L, Pn, V = c["model"], c["B"], c["L"], c["prefix"], c["model"]["vocab"]
+    w = G.make_weights(m, seed=0)
+    ctx, cos, sin = make_ctx(m, w, B, c["max_seq"], L)
+    kv = mulo.alloc_kv(ctx, DEV)
+    dec = OD.DecoderOracle(m, w, cos, sin, B, c["max_seq"], round_bf16=False)
+    prefix = G.uniform_tokens((B, Pn), V, 0, tag=0)
+    dec.forward(prefix, 0)
+    mulo.mulo_verify_forward(ctx, kv, B, Pn, 0, torch.tensor(prefix, device=DEV), None, torch.empty(B, Pn, V, device=DEV))
+    dl = G.normal_logits((B, c["h"] * c["w"], V), c["draft_std"], 0, tag=0)
+    dt = G.sample_categorical(dl, 0, tag=0)
+    tau = 8e-4     # near the median of p(x~) for this random-weight model: both outcomes occur
+    ref = ST.verify_step(dec, Pn, dl, dt, prefix[:, -1], h_blk=c["h"], w=c["w"], r=c["r"], W=c["W"], n0=0,
+                         radius=c["radius"], expand=c["expand"], seed=0, rng_counter=3, accept_mode=1, tau=tau, mode=2)
+    out = decide_buffers(B, L)
+    out["tokens_hi"] = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    out["logits"] = torch.empty(B, L, V, device=DEV)
+    params = mulo.make_params(c["H"], c["W"], 0, L, c["radius"], c["expand"], seed=0, rng_counter=3, resample_mode=2,
+                              accept_mode=mulo.MULO_ACCEPT_TAU, tau=tau)
+    mulo.mulo_verify_step(ctx, kv, B, Pn, params, c["h"], c["w"], c["r"], None, 0, torch.tensor(dt, device=DEV),
+                          torch.tensor(np.ascontiguousarray(prefix[:, -1]), device=DEV), out["tokens_out"],
+                          out["accept"], out["mask"], out["t0"], out["stats"], out["tokens_hi"], out["logits"])
+    torch.cuda.synchronize()
+    g = to_np(out)
+    assert np.abs(g["logits"] - ref["logits"]).max() <= 1e-4
+    assert np.array_equal(g["tokens_hi"], ref["tokens_hi"])
+    # flags may differ only where a logit error of 1e-4 can carry pbar across tau
+    rel = np.expm1(2e-4) + 1e-4
+    movable = np.abs(ref["pbar"].astype(np.float64) - tau) <= rel * tau
+    diff = g["accept"].astype(bool) != ref["accept"].astype(bool)
+    assert not (diff & ~movable).any()
+    say("  tau step: acc %.3f marked %.3f flips %d movable %d" % (ref["accept"].mean(), ref["mask"].mean(), diff.sum(), movable.sum()))
+    assert 0.05 < ref["accept"].mean() < 0.95
+    for b in range(B):
+        if diff[b].any():
+            continue
+        assert np.array_equal(g["mask"][b], ref["mask"][b]) and g["t0"][b] == ref["t0"][b]
+        assert np.array_equal(g["stats"][b, :3], ref["stats"][b, :3])
+        for u in np.flatnonzero(g["tokens_out"][b] != ref["tokens_out"][b]):
+            assert ref["mask"][b, u]
+            assert RS.boundary_distance(RS.integer_weights(ref["p"][b, u]), ref["words"][b, u]) < 4 * rel
+    # and the ratio rule still refuses to run without a draft distribution
+    with pytest.raises(mulo.MuloError) as e:
+        mulo.mulo_verify_step(ctx, kv, B, Pn, mulo.make_params(c["H"], c["W"], 0, L, c["radius"], c["expand"]), c["h"],
+                              c["w"], c["r"], None, 0, torch.tensor(dt, device=DEV),
+                              torch.tensor(np.ascontiguousarray(prefix[:, -1]), device=DEV), out["tokens_out"],
+                              out["accept"], out["mask"], out["t0"], out["stats"], None, None)
+    assert e.value.status == 1

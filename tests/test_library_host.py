@@ -70,7 +70,12 @@ def test_step_param_checks(lib):
     assert ok(**{**base, "radius": -2}) == 3
     assert ok(**{**base, "radius": -1}) == 0        # raster-scan rule
     assert ok(**{**base, "pool_k": 4}) == 1         # pooling without a table
-    assert ok(**{**base, "resample_mode": 2}) == 3
+    assert ok(**{**base, "resample_mode": 2}) == 0  # every marked position re-drawn from p
+    assert ok(**{**base, "resample_mode": 3}) == 3
+    assert ok(**{**base, "accept_mode": 1, "tau": 1e-4}) == 0   # threshold rule (Eq. 5)
+    assert ok(**{**base, "accept_mode": 1, "tau": -1.0}) == 3
+    assert ok(**{**base, "accept_mode": 1, "tau": float("nan")}) == 3
+    assert ok(**{**base, "accept_mode": 2}) == 3
     assert ok(**{**base, "B": 5}) == 2
     assert lib.mulo_check_step_params(C.byref(cfg), 4, None) == 1
 
