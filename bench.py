@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--sigma", type=float, default=None, help="draft-logit noise std (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--profile-all", action="store_true",
+                    help="bracket every kernel class (adds ~3 %% to the step); default: only the roofline kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB read + 1 GiB write element-wise kernel (scale for HBM byte counters)")
     a = ap.parse_args()
@@ -80,6 +82,7 @@ def main():
     import torch
 
     import paper_2601_05149_amd as mulo
+    from paper_2601_05149_amd.binding import PROF_CLASSES
     from workloads import configs as WC
     from workloads import generators as G
 
@@ -151,7 +154,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
     if not a.no_profile:
-        mulo.mulo_profile(ctx, 1)
+        mulo.mulo_profile(ctx, 1 if a.profile_all else 0x100 | PROF_CLASSES.index("gemm_gate_up"))
     t_start = time.perf_counter()
     for i in range(a.steps):
         step(a.warmup + i)

@@ -216,7 +216,10 @@ MULO_API mulo_status mulo_verify_step(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int
  * of HIP events on the context's stream.  mulo_profile_read synchronises the
  * stream, adds up the elapsed time and the launch count per kernel class since
  * the last read, and clears them.  ms and launches are host arrays of
- * MULO_PROF_N entries.  At most 16384 launches are recorded between two reads. */
+ * MULO_PROF_N entries.  At most 16384 launches are recorded between two reads.
+ * enable: 0 = off, 1 = every class, MULO_PROF_ONLY(c) = class c alone (each pair of events
+ * costs a few microseconds of stream time, so a benchmark brackets only what it reports). */
+#define MULO_PROF_ONLY(c) (0x100 | (c))
 enum {
     MULO_PROF_GEMM_QKV = 0,   /* QKV projection + rotary + cache append */
     MULO_PROF_GEMM_OUT = 1,   /* attention output projection + residual */

@@ -34,6 +34,7 @@ struct mulo_ctx {
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
+    uint32_t prof_mask = 0;   // classes that are bracketed
     int prof_n = 0;
     std::vector<hipEvent_t> prof_ev;   // 2 events per recorded launch
     std::vector<int> prof_cls;
@@ -73,7 +74,7 @@ struct ProfScope {
     mulo_ctx* c;
     int i;
     ProfScope(mulo_ctx* ctx, int cls) : c(ctx), i(-1) {
-        if (!c->prof_on || c->prof_n >= PROF_MAX) return;
+        if (!c->prof_on || !((c->prof_mask >> cls) & 1u) || c->prof_n >= PROF_MAX) return;
         i = c->prof_n++;
         c->prof_cls[i] = cls;
         (void)hipEventRecord(c->prof_ev[2 * i], c->st);
@@ -297,6 +298,7 @@ mulo_status mulo_profile(mulo_ctx* ctx, int32_t enable) {
             if (!hip_ok(hipEventCreate(&e))) return MULO_ERR_HIP;
     }
     ctx->prof_on = enable != 0;
+    ctx->prof_mask = (enable & 0x100) ? ((enable & 0xff) < MULO_PROF_N ? 1u << (enable & 0xff) : 0u) : 0xFFFFFFFFu;
     return MULO_OK;
 }
 
