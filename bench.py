@@ -186,6 +186,9 @@ def main():
         if name in flops:
             e.update(bound="mfma", achieved=round(flops[name] / (avg * 1e-3) / 1e12, 1), unit="TFLOP/s")
             e["frac"] = round(e["achieved"] / PEAK_BF16_TFLOPS, 4)
+            if name == "attention":   # K and V rows of every (sequence, head) read once per launch
+                kv_bytes = 2.0 * 2 * d * B * (P + L)
+                e["kv_gbs"] = round(kv_bytes / (avg * 1e-3) / 1e9, 1)
         elif name in byts:
             e.update(bound="hbm", achieved=round(byts[name] / (avg * 1e-3) / 1e9, 1), unit="GB/s")
             e["frac"] = round(e["achieved"] / PEAK_HBM_GBS, 4)
@@ -210,6 +213,7 @@ def main():
                                   "V=%d, radius %d, sigma %.2g" % (c["name"], c["model_name"], B, L, c["H"], c["W"], P, V,
                                                                     c["radius"], sigma),
                       "acceptance_rate": round(acc_rate, 4), "marked_fraction": round(marked, 4)},
+           "accepted_tokens_per_s": round(M * (1.0 - marked) / (ms_per_step * 1e-3), 1),
            "step_tflops": round(fwd_flops / (ms_per_step * 1e-3) / 1e12, 1),
            "step_frac_of_bf16_peak": round(fwd_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
            "roofline": roof, "kernels": kernels}

@@ -267,3 +267,33 @@ def test_tau_rule_limits_and_errors_on_device():
         with pytest.raises(mulo.MuloError) as e:
             run_decide(ctx, zp, None, toks, tau=1e-3, **bad)
         assert e.value.status == 1
+
+
+def test_sampler_words_equal_the_oracle_generator_on_2_pow_20_counters():
+    """Uniform target distribution over V = 2^16 entries, everything rejected (threshold above 1) and re-drawn
+    from p: the integer inverse CDF then returns the top 16 bits of each position's Philox word, so the
+    device generator (counter layout, key schedule, rounds) is compared with the oracle's on 2^20 counters."""
+    from oracle import philox as PH
+    from oracle import resample as RS
+    B, L, V = 4, 1024, 65536
+    ctx = decide_ctx(V, B, L)
+    z = torch.zeros(B, L, V, device=DEV)
+    toks = torch.zeros(B, L, dtype=torch.int32, device=DEV)
+    out = decide_buffers(B, L)
+    # closed form of the draw for equal weights, checked against the oracle's sampler on a few words
+    Wi = RS.integer_weights(np.full(V, 1.0 / V, np.float32))
+    for wd in (0, 1, 65535, 65536, 0x7FFFFFFF, 0x80000000, 0xFFFFFFFF, 0x12345678):
+        assert RS.draw(Wi, wd) == wd >> 16
+    seed = 0x9E3779B97F4A7C15
+    n_bad = 0
+    for c in range(256):
+        ctr = (c << 40) | (c * 2654435761 % (1 << 32))          # low and high counter words both vary
+        params = mulo.make_params(32, 32, 0, L, 1, 1, resample_mode=2, seed=seed, rng_counter=ctr,
+                                  accept_mode=mulo.MULO_ACCEPT_TAU, tau=1.5)
+        mulo.mulo_accept_local_resample(ctx, B, params, z, None, None, 0, toks, out["tokens_out"], out["accept"],
+                                        out["mask"], out["t0"], out["stats"], None)
+        got = out["tokens_out"].cpu().numpy()
+        words = PH.step_words(seed, ctr, PH.STREAM_SAMPLE, B, L)
+        n_bad += int((got != (words >> 16).astype(np.int64)).sum())
+    say("  sampler words: %d of %d positions differ" % (n_bad, 256 * B * L))
+    assert n_bad == 0
