@@ -416,7 +416,8 @@ void dispatch(const GemmArgs& g, hipStream_t st) {
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
     const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
-                      (int64_t)g.K * 256 * 2 < (1ll << 31);
+                      (int64_t)g.K * 256 * 2 < (1ll << 31) &&
+                     (int64_t)(g.M / 256) * (g.N / 256) * 4 >= 3 * (int64_t)cu_count();   // enough 256x256 tiles to fill the chip
     if (big) {
         // Whole rounds of 256x256 tiles, one tile per CU and round.  A last round that would leave more than
         // half of the CUs idle is cut off and run as 128x256 tiles (twice as many workgroups, half the work each).
