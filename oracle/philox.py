@@ -25,6 +25,7 @@ _S32 = np.uint64(32)
 
 STREAM_ACCEPT = 0
 STREAM_SAMPLE = 1
+STREAM_SEQUENTIAL = 2   # sequential re-sampling (Alg. 1 Step 6)
 
 
 def philox4x32(c0, c1, c2, c3, k0, k1, rounds=10):

@@ -75,3 +75,36 @@ def verify_step(decoder, P, draft_lo, draft_tokens_lo, prev_tokens, *, h_blk, w,
                  seed=seed, rng_counter=rng_counter, nbr=nbr, mode=mode, accept_mode=accept_mode, tau=tau)
     out.update(tokens_hi=tokens_hi, q_lo=q_lo, q_row=q_row, logits=logits)
     return out
+
+
+def resample_sequential(decoder, P, tokens, mask, t0, prev_tokens, *, seed=0, rng_counter=0):
+    """Alg. 1 Step 6: the marked positions R_X are visited in increasing order and each gets a
+    sample of the target model given the prefix and ALL earlier positions of the block as they
+    stand after the earlier re-draws:  x_k ~ M_p(x | x_0 .. x_{k-1}).
+
+    decoder: oracle decoder whose cache rows [0, P) are valid (rows of the block may hold anything:
+    every row from the first marked position on is recomputed here, one token at a time, because
+    its input or its context has changed).  tokens: int [B, L] block after the parallel step (draft
+    tokens; marked positions are overwritten); mask: [B, L]; t0: [B] first rejected position (L if
+    none); prev_tokens: [B].  The draw uses the integer inverse CDF of p (float32 probabilities)
+    with the Philox word of stream 2 at (position, batch element).
+    Returns (tokens_out int32 [B, L], logits float64 [B, L, V] with rows before min(t0) left at 0).
+    """
+    tok = np.asarray(tokens).astype(np.int32).copy()
+    mask = np.asarray(mask).astype(bool)
+    B, L = tok.shape
+    words = PH.step_words(seed, rng_counter, PH.STREAM_SEQUENTIAL, B, L)
+    start = int(np.min(t0))
+    logits = None
+    for u in range(start, L):
+        inp = np.asarray(prev_tokens).reshape(B, 1) if u == 0 else tok[:, u - 1:u]
+        z = decoder.forward(inp.astype(np.int32), P + u).numpy()[:, 0]       # [B, V]; rewrites cache row P + u
+        if logits is None:
+            logits = np.zeros((B, L, z.shape[-1]))
+        logits[:, u] = z
+        for b in range(B):
+            if mask[b, u]:
+                tok[b, u] = RS.draw(RS.integer_weights(A.target_probs(z[b])), words[b, u])
+    if logits is None:
+        logits = np.zeros((B, L, 0))
+    return tok, logits

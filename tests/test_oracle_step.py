@@ -2,7 +2,10 @@
 tie the stages together.  CPU only."""
 import numpy as np
 
+from oracle import accept as A
 from oracle import decoder as D
+from oracle import philox as PH
+from oracle import resample as RS
 from oracle import step as ST
 from workloads import configs as C
 from workloads import generators as G
@@ -43,3 +46,71 @@ def test_tiny_step_invariants():
     assert np.array_equal(again["tokens_out"], out["tokens_out"])
     _, _, _, other = _tiny_step(rng_counter=1)
     assert not np.array_equal(other["accept"], out["accept"])
+
+
+# ------------------------------------------------------------------ sequential re-sampling (Alg. 1 Step 6)
+def _seq_setup(seed=4):
+    from oracle import decoder as OD
+    m = dict(n_layers=2, d_model=32, n_heads=2, head_dim=16, d_ffn=48, vocab=24, dtype="f32", rms_eps=1e-5)
+    w = G.make_weights(m, seed=seed, threads=1)
+    cos, sin = G.rope_table(64, m["head_dim"])
+    mk = lambda: OD.DecoderOracle(m, w, cos, sin, 2, 64, round_bf16=False)
+    return m, mk
+
+
+def test_sequential_resampling_is_ancestral_sampling_of_the_target():
+    """With every position marked, Step 6 is plain autoregressive sampling: position u is the inverse-CDF
+    draw from the target's next-token distribution given the prefix and the tokens drawn before it.  Checked
+    against a from-scratch recomputation (a fresh decoder run over the whole final sequence)."""
+    m, mk = _seq_setup()
+    V, B, Pn, L = m["vocab"], 2, 5, 12
+    prefix = G.uniform_tokens((B, Pn), V, 1, tag=0)
+    dec = mk(); dec.forward(prefix, 0)
+    draft = G.uniform_tokens((B, L), V, 2, tag=0)
+    out, _ = ST.resample_sequential(dec, Pn, draft, np.ones((B, L), bool), np.zeros(B, int), prefix[:, -1], seed=9, rng_counter=3)
+    # teacher-forced check: one block pass over [prefix, out] gives every conditional at once
+    ref = mk()
+    full = np.concatenate([prefix, out], axis=1)
+    z = ref.forward(full[:, :-1], 0).numpy()          # logits row j: distribution of token j + 1
+    words = PH.step_words(9, 3, PH.STREAM_SEQUENTIAL, B, L)
+    for b in range(B):
+        for u in range(L):
+            p = A.target_probs(z[b, Pn - 1 + u])
+            assert out[b, u] == RS.draw(RS.integer_weights(p), words[b, u])
+
+
+def test_sequential_resampling_keeps_unmarked_tokens_and_refreshes_their_context():
+    m, mk = _seq_setup()
+    V, B, Pn, L = m["vocab"], 2, 4, 10
+    prefix = G.uniform_tokens((B, Pn), V, 3, tag=0)
+    draft = G.uniform_tokens((B, L), V, 4, tag=0)
+    mask = np.zeros((B, L), bool); mask[0, [3, 4, 8]] = True; mask[1, [6]] = True
+    t0 = np.array([3, 6])
+    dec = mk(); dec.forward(prefix, 0)
+    dec.forward(np.concatenate([prefix[:, -1:], draft[:, :-1]], axis=1), Pn)     # the verify pass filled the block rows
+    out, _ = ST.resample_sequential(dec, Pn, draft, mask, t0, prefix[:, -1], seed=1, rng_counter=0)
+    assert np.array_equal(out[~mask], draft[~mask])
+    # nothing before the first marked position of a sequence moves, and the re-draws are samples of the
+    # conditionals of the FINAL sequence (later marked positions see the earlier re-draws)
+    ref = mk()
+    z = ref.forward(np.concatenate([prefix, out], axis=1)[:, :-1], 0).numpy()
+    words = PH.step_words(1, 0, PH.STREAM_SEQUENTIAL, B, L)
+    for b, u in zip(*np.nonzero(mask)):
+        assert out[b, u] == RS.draw(RS.integer_weights(A.target_probs(z[b, Pn - 1 + u])), words[b, u])
+    # and afterwards the block's cache rows from the first marked position on equal those of a fresh pass
+    # over the final inputs [prev, out_0 .. out_{L-2}]
+    fresh = mk(); fresh.forward(prefix, 0)
+    fresh.forward(np.concatenate([prefix[:, -1:], out[:, :-1]], axis=1), Pn)
+    lo = int(t0.min())
+    assert np.allclose(dec.k[:, :B, Pn + lo:Pn + L].numpy(), fresh.k[:, :B, Pn + lo:Pn + L].numpy(), atol=1e-9)
+    assert np.allclose(dec.v[:, :B, Pn + lo:Pn + L].numpy(), fresh.v[:, :B, Pn + lo:Pn + L].numpy(), atol=1e-9)
+
+
+def test_sequential_resampling_with_nothing_marked_is_the_identity():
+    m, mk = _seq_setup()
+    V, B, Pn, L = m["vocab"], 2, 4, 6
+    prefix = G.uniform_tokens((B, Pn), V, 5, tag=0)
+    draft = G.uniform_tokens((B, L), V, 6, tag=0)
+    dec = mk(); dec.forward(prefix, 0)
+    out, _ = ST.resample_sequential(dec, Pn, draft, np.zeros((B, L), bool), np.array([L, L]), prefix[:, -1])
+    assert np.array_equal(out, draft)
