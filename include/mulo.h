@@ -211,6 +211,21 @@ MULO_API mulo_status mulo_verify_step(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int
                              int32_t *tokens_out, uint8_t *accept, uint8_t *mask, int32_t *t0,
                              int32_t *stats, int32_t *tokens_hi, float *logits);
 
+/* Sequential re-sampling of the marked positions (Alg. 1 Step 6): for u = u_start .. L-1 in order, the
+ * target is evaluated on the single input token that precedes position u ([prev, x_0 .. x_{L-2}][u], taken
+ * from `tokens` as it stands) against cache rows [0, P+u), cache row P+u is rewritten, and where mask[b,u]
+ * is set tokens[b,u] is replaced by a draw from softmax of that logit row (integer inverse CDF, Philox
+ * stream 2 at (u, b)); unmarked positions keep their token but their cache row is refreshed, because their
+ * context changed.  u_start must be <= the first marked position of every sequence (0 is always valid; the
+ * smallest t0 of the parallel step is the useful value).  L - u_start single-token forwards are enqueued.
+ *   prev_tokens device int32 [B]; mask device uint8 [B, L]; tokens device int32 [B, L] (in/out)
+ *   logits      device float32 [B, L, vocab] (out) or NULL: the logit rows u_start .. L-1 that were used
+ * Errors: B > max_batch, P + L > max_seq -> MULO_ERR_SHAPE; u_start outside [0, L] -> MULO_ERR_RANGE. */
+MULO_API mulo_status mulo_resample_sequential(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int32_t P, int32_t L,
+                                     int32_t u_start, uint64_t seed, uint64_t rng_counter,
+                                     const int32_t *prev_tokens, const uint8_t *mask, int32_t *tokens,
+                                     float *logits);
+
 /* Optional per-kernel timing (measurement aid, not part of the method).  While
  * enabled, every kernel launch of the entry points above is bracketed by a pair
  * of HIP events on the context's stream.  mulo_profile_read synchronises the

@@ -17,7 +17,8 @@ STATUS_NAMES = {0: "MULO_OK", 1: "MULO_ERR_NULL", 2: "MULO_ERR_SHAPE", 3: "MULO_
                 4: "MULO_ERR_ALLOC", 5: "MULO_ERR_HIP", 6: "MULO_ERR_UNSUPPORTED"}
 EXPORTS = ["mulo_status_string", "mulo_check_model_cfg", "mulo_check_step_params", "mulo_workspace_bytes",
            "mulo_create", "mulo_destroy", "mulo_upsample_draft", "mulo_verify_forward",
-           "mulo_accept_local_resample", "mulo_verify_step", "mulo_profile", "mulo_profile_read"]
+           "mulo_accept_local_resample", "mulo_verify_step", "mulo_resample_sequential", "mulo_profile",
+           "mulo_profile_read"]
 
 
 class MuloError(RuntimeError):
@@ -75,6 +76,7 @@ def load_library():
     lib.mulo_accept_local_resample.argtypes = [P, I32, C.POINTER(StepParams), P, P, P, I64, P, P, P, P, P, P, P]
     lib.mulo_verify_step.argtypes = [P, C.POINTER(KV), I32, I32, C.POINTER(StepParams), I32, I32, I32, P, I32,
                                      P, P, P, P, P, P, P, P, P]
+    lib.mulo_resample_sequential.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P]
     lib.mulo_profile.argtypes = [P, I32]
     lib.mulo_profile_read.argtypes = [P, C.POINTER(C.c_float), C.POINTER(I32)]
     for n in EXPORTS:
@@ -194,6 +196,14 @@ def mulo_verify_step(ctx, kv, B, P, params, h_blk, w, r, draft, input_is_probs, 
         _ptr(draft_tokens, i32), _ptr(prev_tokens, i32), _ptr(tokens_out, i32), _ptr(accept, u8),
         _ptr(mask, u8), _ptr(t0, i32), _ptr(stats, i32), _ptr(tokens_hi, i32, True), _ptr(logits, f32, True)),
         "mulo_verify_step")
+
+
+def mulo_resample_sequential(ctx, kv, B, P, L, u_start, seed, rng_counter, prev_tokens, mask, tokens, logits=None):
+    f32, i32, u8 = torch.float32, torch.int32, torch.uint8
+    kvs = KV(_ptr(kv[0], ctx.tdtype), _ptr(kv[1], ctx.tdtype))
+    _check(load_library().mulo_resample_sequential(
+        ctx.handle, C.byref(kvs), B, P, L, u_start, C.c_uint64(seed), C.c_uint64(rng_counter), _ptr(prev_tokens, i32),
+        _ptr(mask, u8), _ptr(tokens, i32), _ptr(logits, f32, True)), "mulo_resample_sequential")
 
 
 PROF_CLASSES = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention", "norm_embed",

@@ -281,6 +281,79 @@ __device__ __forceinline__ void weights4(const float4 z, const float4 qv, float 
     w[2] = (unsigned long long)__fmul_rn(p2, S); w[3] = (unsigned long long)__fmul_rn(p3, S);
 }
 
+// Integer-CDF draw of one row by one workgroup: W(x) = floor(w(x) 2^40) with w = max(0, p - q) (or p when
+// use_p), T = (word * tot) >> 32, token = first x whose inclusive prefix exceeds T; an empty residual falls
+// back to p.  The token is stored to *out by the lane that finds it.
+__device__ __forceinline__ void cdf_draw(const float4* __restrict__ z4, const float4* __restrict__ q4, float m,
+                                         float inv, bool use_p, uint32_t word, int V, int fallback_tok,
+                                         int32_t* out, unsigned long long* chunk, int* s_retry) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int nv4 = V >> 2, nchunks = (nv4 + 63) >> 6;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        for (int base = 0; base < nv4; base += TPB) {
+            const int idx = base + tid;
+            unsigned long long s = 0;
+            if (idx < nv4) {
+                unsigned long long w[4];
+                weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                s = (w[0] + w[1]) + (w[2] + w[3]);
+            }
+            s = wave_sum_u64(s);
+            const int c = (base >> 6) + wv;
+            if (lane == 0 && c < nchunks) chunk[c] = s;
+        }
+        if (tid == 0) *s_retry = 0;
+        __syncthreads();
+        if (wv == 0) {
+            unsigned long long tot = 0;
+            for (int c0 = 0; c0 < nchunks; c0 += 64) tot += (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
+            tot = wave_sum_u64(tot);
+            if (tot == 0) {
+                if (lane == 0) *s_retry = 1;  // empty residual: draw from p instead
+            } else {
+                const unsigned long long T = __umul64hi((unsigned long long)word << 32, tot);
+                unsigned long long run = 0, before = 0;
+                int cidx = nchunks - 1;
+                for (int c0 = 0; c0 < nchunks; c0 += 64) {
+                    const unsigned long long v = (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
+                    const unsigned long long incl = wave_scan_u64(v, lane) + run;
+                    const unsigned long long hit = __ballot(incl > T);
+                    if (hit) {
+                        const int f = __ffsll((long long)hit) - 1;
+                        cidx = c0 + f;
+                        before = __shfl(incl - v, f);
+                        break;
+                    }
+                    run = __shfl(incl, 63);
+                }
+                // inside the chunk: 64 lanes x 4 entries, same weights as above
+                const int idx = cidx * 64 + lane;
+                unsigned long long w[4] = {0, 0, 0, 0};
+                if (idx < nv4) weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                const unsigned long long s = (w[0] + w[1]) + (w[2] + w[3]);
+                const unsigned long long incl = wave_scan_u64(s, lane) + before;
+                const unsigned long long hit = __ballot(incl > T);
+                const int f = hit ? __ffsll((long long)hit) - 1 : 63;
+                if (lane == f) {
+                    unsigned long long cum = incl - s;
+                    int tok = fallback_tok;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        cum += w[e];
+                        if (cum > T) { tok = idx * 4 + e; break; }
+                    }
+                    *out = clamp_tok(tok, V);
+                }
+            }
+        }
+        __syncthreads();
+        if (!*s_retry || use_p) break;
+        use_p = true;
+        __syncthreads();
+    }
+}
+
 __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
     __shared__ unsigned long long chunk[MAX_CHUNKS];
     __shared__ int s_retry;
@@ -314,81 +387,42 @@ __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
     }
     if (!marked) return;
 
-    // Residual draw through an integer CDF: W(x) = floor(max(0, p - q) 2^40),
-    // T = (word * tot) >> 32, token = first x whose inclusive prefix exceeds T.
-    const int V = a.V, nv4 = V >> 2, nchunks = (nv4 + 63) >> 6;
+    // Residual draw through the integer CDF
+    const int V = a.V;
     const float4* z4 = reinterpret_cast<const float4*>(a.logits + row * V);
     const int qr = a.q_row ? a.q_row[t] : t;
-    bool use_p = a.resample_mode == 2 || ((a.resample_mode == 1) && a.accept[row] != 0);
+    const bool use_p = a.resample_mode == 2 || ((a.resample_mode == 1) && a.accept[row] != 0);
     // the draft row is read only for residual weights (it may be absent when every draw is from p)
     const float4* q4 = a.q ? reinterpret_cast<const float4*>(a.q + b * a.q_batch_stride + (int64_t)qr * V) : z4;
-    const float m = a.rowmax[row], inv = a.rowinv[row];
     const uint32_t word = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24 | (1u << 24),
                                        a.key0, a.key1);
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    cdf_draw(z4, q4, a.rowmax[row], a.rowinv[row], use_p, word, V, draft, &a.tokens_out[row], chunk, &s_retry);
+}
 
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        for (int base = 0; base < nv4; base += TPB) {
-            const int idx = base + tid;
-            unsigned long long s = 0;
-            if (idx < nv4) {
-                unsigned long long w[4];
-                weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
-                s = (w[0] + w[1]) + (w[2] + w[3]);
-            }
-            s = wave_sum_u64(s);
-            const int c = (base >> 6) + wv;
-            if (lane == 0 && c < nchunks) chunk[c] = s;
-        }
-        if (tid == 0) s_retry = 0;
-        __syncthreads();
-        if (wv == 0) {
-            unsigned long long tot = 0;
-            for (int c0 = 0; c0 < nchunks; c0 += 64) tot += (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
-            tot = wave_sum_u64(tot);
-            if (tot == 0) {
-                if (lane == 0) s_retry = 1;  // empty residual: draw from p instead
-            } else {
-                const unsigned long long T = __umul64hi((unsigned long long)word << 32, tot);
-                unsigned long long run = 0, before = 0;
-                int cidx = nchunks - 1;
-                for (int c0 = 0; c0 < nchunks; c0 += 64) {
-                    const unsigned long long v = (c0 + lane < nchunks) ? chunk[c0 + lane] : 0ull;
-                    const unsigned long long incl = wave_scan_u64(v, lane) + run;
-                    const unsigned long long hit = __ballot(incl > T);
-                    if (hit) {
-                        const int f = __ffsll((long long)hit) - 1;
-                        cidx = c0 + f;
-                        before = __shfl(incl - v, f);
-                        break;
-                    }
-                    run = __shfl(incl, 63);
-                }
-                // inside the chunk: 64 lanes x 4 entries, same weights as above
-                const int idx = cidx * 64 + lane;
-                unsigned long long w[4] = {0, 0, 0, 0};
-                if (idx < nv4) weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
-                const unsigned long long s = (w[0] + w[1]) + (w[2] + w[3]);
-                const unsigned long long incl = wave_scan_u64(s, lane) + before;
-                const unsigned long long hit = __ballot(incl > T);
-                const int f = hit ? __ffsll((long long)hit) - 1 : 63;
-                if (lane == f) {
-                    unsigned long long cum = incl - s;
-                    int tok = draft;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        cum += w[e];
-                        if (cum > T) { tok = idx * 4 + e; break; }
-                    }
-                    a.tokens_out[row] = clamp_tok(tok, V);
-                }
-            }
-        }
-        __syncthreads();
-        if (!s_retry || use_p) break;
-        use_p = true;
-        __syncthreads();
-    }
+// ---- Alg. 1 Step 6, one position: inputs of the single-token forward, then the draw from p ----
+__global__ void k_seq_input(const int32_t* __restrict__ prev, const int32_t* __restrict__ tokens,
+                            int32_t* __restrict__ inp, int B, int L, int u) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) inp[b] = u == 0 ? prev[b] : tokens[(int64_t)b * L + u - 1];
+}
+
+// one workgroup per sequence: if position u is marked, tokens[b, u] ~ softmax(logits[b, :])
+__global__ __launch_bounds__(TPB) void k_seq_draw(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
+                                                  int32_t* __restrict__ tokens, int L, int V, int u, uint32_t key0,
+                                                  uint32_t key1, uint32_t ctr_lo, uint32_t ctr_hi24) {
+    __shared__ unsigned long long chunk[MAX_CHUNKS];
+    __shared__ int s_retry;
+    __shared__ float red[WAVES];
+    const int b = blockIdx.x;
+    if (!mask[(int64_t)b * L + u]) return;   // uniform over the workgroup
+    const float* z = logits + (int64_t)b * V;
+    RowRegs<0> none;
+    float m, inv;
+    row_stats<0>(z, V, none, red, m, inv);
+    const uint32_t word = philox_word0((uint32_t)u, (uint32_t)b, ctr_lo, ctr_hi24 | (2u << 24), key0, key1);
+    const float4* z4 = reinterpret_cast<const float4*>(z);
+    int32_t* out = tokens + (int64_t)b * L + u;
+    cdf_draw(z4, z4, m, inv, true, word, V, *out, out, chunk, &s_retry);
 }
 
 template <int NV4>
@@ -437,6 +471,17 @@ void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t*
     const int64_t n = (int64_t)B * L;
     hipLaunchKernelGGL(k_shift_inputs, dim3((unsigned)((n + TPB - 1) / TPB)), dim3(TPB), 0, st, prev,
                        tokens_hi, inputs, B, L);
+}
+
+void launch_seq_input(const int32_t* prev, const int32_t* tokens, int32_t* inp, int B, int L, int u, hipStream_t st) {
+    hipLaunchKernelGGL(k_seq_input, dim3((B + 63) / 64), dim3(64), 0, st, prev, tokens, inp, B, L, u);
+}
+
+void launch_seq_draw(const float* logits, const uint8_t* mask, int32_t* tokens, int B, int L, int V, int u,
+                     uint64_t seed, uint64_t rng_counter, hipStream_t st) {
+    hipLaunchKernelGGL(k_seq_draw, dim3(B), dim3(TPB), 0, st, logits, mask, tokens, L, V, u,
+                       (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), (uint32_t)(rng_counter & 0xFFFFFFFFu),
+                       (uint32_t)((rng_counter >> 32) & 0xFFFFFFu));
 }
 
 void launch_accept(const DecideArgs& a, hipStream_t st) {

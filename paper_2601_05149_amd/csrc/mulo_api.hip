@@ -390,4 +390,25 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     return check_launch();
 }
 
+mulo_status mulo_resample_sequential(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, int32_t L, int32_t u_start,
+                                     uint64_t seed, uint64_t rng_counter, const int32_t* prev_tokens,
+                                     const uint8_t* mask, int32_t* tokens, float* logits) {
+    if (!ctx || !prev_tokens || !mask || !tokens) return MULO_ERR_NULL;
+    if (L < 1 || u_start < 0 || u_start > L) return MULO_ERR_RANGE;
+    mulo_status s = check_forward_args(ctx, kv, B, 1, P + L - 1);
+    if (s != MULO_OK) return s;
+    if (P < 0) return MULO_ERR_RANGE;
+    const int V = ctx->cfg.vocab;
+    mulo_ctx* c = ctx;
+    for (int u = u_start; u < L; ++u) {
+        { PROF(MULO_PROF_OTHER); launch_seq_input(prev_tokens, tokens, ctx->inputs, B, L, u, ctx->st); }
+        enqueue_forward(ctx, kv, B, 1, P + u, ctx->inputs, nullptr, ctx->logits);
+        { PROF(MULO_PROF_MASK_SAMPLE); launch_seq_draw(ctx->logits, mask, tokens, B, L, V, u, seed, rng_counter, ctx->st); }
+        if (logits)
+            for (int b = 0; b < B; ++b)
+                launch_copy_rows(ctx->logits + (int64_t)b * V, logits + ((int64_t)b * L + u) * V, V, ctx->st);
+    }
+    return check_launch();
+}
+
 }  // extern "C"

@@ -49,13 +49,23 @@ def test_tiny_step_invariants():
 
 
 # ------------------------------------------------------------------ sequential re-sampling (Alg. 1 Step 6)
+# Convention of the step: the cache holds rows [0, P) and `prev` is the token that FOLLOWS them (its own row
+# is written by the step at row P).  So a context "prefix" of n tokens is prefilled as prefix[:, :-1]
+# (P = n - 1) with prev = prefix[:, -1].
 def _seq_setup(seed=4):
     from oracle import decoder as OD
     m = dict(n_layers=2, d_model=32, n_heads=2, head_dim=16, d_ffn=48, vocab=24, dtype="f32", rms_eps=1e-5)
-    w = G.make_weights(m, seed=seed, threads=1)
+    w = G.make_weights(m, seed=seed, std=0.35, threads=1)      # large enough for peaked, context-dependent distributions
     cos, sin = G.rope_table(64, m["head_dim"])
     mk = lambda: OD.DecoderOracle(m, w, cos, sin, 2, 64, round_bf16=False)
     return m, mk
+
+
+def _teacher_forced(mk, prefix, out):
+    """Logit rows of the conditionals of out[:, u] given prefix and out[:, :u], by one block pass."""
+    ref = mk()
+    z = ref.forward(np.concatenate([prefix, out], axis=1)[:, :-1], 0).numpy()
+    return z[:, prefix.shape[1] - 1:]
 
 
 def test_sequential_resampling_is_ancestral_sampling_of_the_target():
@@ -65,18 +75,19 @@ def test_sequential_resampling_is_ancestral_sampling_of_the_target():
     m, mk = _seq_setup()
     V, B, Pn, L = m["vocab"], 2, 5, 12
     prefix = G.uniform_tokens((B, Pn), V, 1, tag=0)
-    dec = mk(); dec.forward(prefix, 0)
+    dec = mk(); dec.forward(prefix[:, :-1], 0)
     draft = G.uniform_tokens((B, L), V, 2, tag=0)
-    out, _ = ST.resample_sequential(dec, Pn, draft, np.ones((B, L), bool), np.zeros(B, int), prefix[:, -1], seed=9, rng_counter=3)
-    # teacher-forced check: one block pass over [prefix, out] gives every conditional at once
-    ref = mk()
-    full = np.concatenate([prefix, out], axis=1)
-    z = ref.forward(full[:, :-1], 0).numpy()          # logits row j: distribution of token j + 1
+    out, zs = ST.resample_sequential(dec, Pn - 1, draft, np.ones((B, L), bool), np.zeros(B, int), prefix[:, -1], seed=9, rng_counter=3)
+    z = _teacher_forced(mk, prefix, out)
+    assert np.abs(zs - z).max() < 1e-9                    # the rows it sampled from are those conditionals
+    assert A.target_probs(z).max(-1).mean() > 0.2         # the distributions are far from uniform ...
+    assert np.abs(z[:, 1:] - z[:, :-1]).max() > 1.0       # ... and depend on the context
     words = PH.step_words(9, 3, PH.STREAM_SEQUENTIAL, B, L)
     for b in range(B):
         for u in range(L):
-            p = A.target_probs(z[b, Pn - 1 + u])
-            assert out[b, u] == RS.draw(RS.integer_weights(p), words[b, u])
+            assert out[b, u] == RS.draw(RS.integer_weights(A.target_probs(z[b, u])), words[b, u])
+    # a dropped context refresh would show: re-running with the stale draft as context gives other logits
+    assert np.abs(_teacher_forced(mk, prefix, draft) - z)[:, 1:].max() > 0.1
 
 
 def test_sequential_resampling_keeps_unmarked_tokens_and_refreshes_their_context():
@@ -86,24 +97,26 @@ def test_sequential_resampling_keeps_unmarked_tokens_and_refreshes_their_context
     draft = G.uniform_tokens((B, L), V, 4, tag=0)
     mask = np.zeros((B, L), bool); mask[0, [3, 4, 8]] = True; mask[1, [6]] = True
     t0 = np.array([3, 6])
-    dec = mk(); dec.forward(prefix, 0)
-    dec.forward(np.concatenate([prefix[:, -1:], draft[:, :-1]], axis=1), Pn)     # the verify pass filled the block rows
-    out, _ = ST.resample_sequential(dec, Pn, draft, mask, t0, prefix[:, -1], seed=1, rng_counter=0)
+    P = Pn - 1
+    dec = mk(); dec.forward(prefix[:, :-1], 0)
+    dec.forward(np.concatenate([prefix[:, -1:], draft[:, :-1]], axis=1), P)     # the verify pass filled the block rows
+    out, zs = ST.resample_sequential(dec, P, draft, mask, t0, prefix[:, -1], seed=1, rng_counter=0)
     assert np.array_equal(out[~mask], draft[~mask])
-    # nothing before the first marked position of a sequence moves, and the re-draws are samples of the
-    # conditionals of the FINAL sequence (later marked positions see the earlier re-draws)
-    ref = mk()
-    z = ref.forward(np.concatenate([prefix, out], axis=1)[:, :-1], 0).numpy()
+    # the re-draws are samples of the conditionals of the FINAL sequence (later marked positions see the earlier re-draws)
+    z = _teacher_forced(mk, prefix, out)
+    lo = int(t0.min())
+    assert np.abs(zs[:, lo:] - z[:, lo:]).max() < 1e-9
     words = PH.step_words(1, 0, PH.STREAM_SEQUENTIAL, B, L)
     for b, u in zip(*np.nonzero(mask)):
-        assert out[b, u] == RS.draw(RS.integer_weights(A.target_probs(z[b, Pn - 1 + u])), words[b, u])
-    # and afterwards the block's cache rows from the first marked position on equal those of a fresh pass
-    # over the final inputs [prev, out_0 .. out_{L-2}]
-    fresh = mk(); fresh.forward(prefix, 0)
-    fresh.forward(np.concatenate([prefix[:, -1:], out[:, :-1]], axis=1), Pn)
-    lo = int(t0.min())
-    assert np.allclose(dec.k[:, :B, Pn + lo:Pn + L].numpy(), fresh.k[:, :B, Pn + lo:Pn + L].numpy(), atol=1e-9)
-    assert np.allclose(dec.v[:, :B, Pn + lo:Pn + L].numpy(), fresh.v[:, :B, Pn + lo:Pn + L].numpy(), atol=1e-9)
+        assert out[b, u] == RS.draw(RS.integer_weights(A.target_probs(z[b, u])), words[b, u])
+    # afterwards the block's cache rows equal those of a fresh pass over the final inputs [prev, out_0 .. out_{L-2}]
+    fresh = mk(); fresh.forward(prefix[:, :-1], 0)
+    fresh.forward(np.concatenate([prefix[:, -1:], out[:, :-1]], axis=1), P)
+    assert np.allclose(dec.k[:, :B, :P + L].numpy(), fresh.k[:, :B, :P + L].numpy(), atol=1e-9)
+    assert np.allclose(dec.v[:, :B, :P + L].numpy(), fresh.v[:, :B, :P + L].numpy(), atol=1e-9)
+    stale = mk(); stale.forward(prefix[:, :-1], 0)
+    stale.forward(np.concatenate([prefix[:, -1:], draft[:, :-1]], axis=1), P)
+    assert np.abs(stale.k[:, :B, P + lo + 1:P + L].numpy() - fresh.k[:, :B, P + lo + 1:P + L].numpy()).max() > 1e-3
 
 
 def test_sequential_resampling_with_nothing_marked_is_the_identity():
@@ -111,6 +124,6 @@ def test_sequential_resampling_with_nothing_marked_is_the_identity():
     V, B, Pn, L = m["vocab"], 2, 4, 6
     prefix = G.uniform_tokens((B, Pn), V, 5, tag=0)
     draft = G.uniform_tokens((B, L), V, 6, tag=0)
-    dec = mk(); dec.forward(prefix, 0)
-    out, _ = ST.resample_sequential(dec, Pn, draft, np.zeros((B, L), bool), np.array([L, L]), prefix[:, -1])
+    dec = mk(); dec.forward(prefix[:, :-1], 0)
+    out, _ = ST.resample_sequential(dec, Pn - 1, draft, np.zeros((B, L), bool), np.array([L, L]), prefix[:, -1])
     assert np.array_equal(out, draft)
