@@ -411,8 +411,135 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
     hipLaunchKernelGGL(kern, dim3(total < resident ? total : resident), dim3(WGM * WGN * 64), lds, st, g);
 }
 
+// ---- up to 32 tokens (single-token decoding of a few sequences): weight-streaming kernel ------------
+// The work is reading every weight once, so nothing is staged: a workgroup owns 32 output columns (for
+// gate|up: 32 feed-forward columns = 32 gate rows + 32 up rows), its 8 wavefronts split K, and every lane
+// feeds MFMAs straight from global memory.  The k-slices of a 64-deep block are dealt so that a lane reads
+// 64 contiguous bytes of one weight row (lane half lh owns k in [32 lh, 32 lh + 32) of the block; MFMA step
+// j takes its j-th 16 bytes, the token operand follows the same deal), i.e. a wavefront reads whole 128-byte
+// lines of 32 rows.  The tokens are the MFMA's lane dimension (lanes m >= M contribute zeros and issue no
+// loads), so the accumulators come out as D[column][token] like in the tiled kernel; the 8 partial sums are
+// added in a fixed order through LDS and 512 threads apply the epilogue to pairs of adjacent columns.
+template <int EPI>
+__global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
+    __shared__ float part[8][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
+    const int n_blk = blockIdx.x * 32;     // first output column (gate|up: first feed-forward column)
+    const int nblk = g.K / 64, per = (nblk + 7) / 8;
+    const int kb0 = wave * per, kb1 = kb0 + per < nblk ? kb0 + per : nblk;
+
+    // weight row(s) of this lane
+    const bf16* w0;
+    const bf16* w1 = nullptr;
+    {
+        int r = n_blk + l32;
+        if constexpr (EPI == EPI_QK) {
+            const int seg = n_blk / g.d;                       // a block never straddles q | k (d % 32 == 0)
+            w0 = (seg == 0 ? g.W0 : g.W1) + (int64_t)(r - seg * g.d) * g.K;
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            const int f = g.N / 2;
+            r = r < f ? r : f - 1;
+            w0 = g.W0 + (int64_t)r * g.K;
+            w1 = g.W1 + (int64_t)r * g.K;
+        } else {
+            r = r < g.N ? r : g.N - 1;
+            w0 = g.W0 + (int64_t)r * g.K;
+        }
+    }
+    const bool has_x = l32 < g.M;
+    const bf16* xp = g.A + (int64_t)(has_x ? l32 : 0) * g.K + lh * 32;
+    w0 += lh * 32;
+    if constexpr (EPI == EPI_SWIGLU) w1 += lh * 32;
+
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int kb = kb0; kb < kb1; ++kb) {
+        u32x4 wa[4], wb[4], xv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wa[j] = *reinterpret_cast<const u32x4*>(w0 + kb * 64 + j * 8);
+        if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wb[j] = *reinterpret_cast<const u32x4*>(w1 + kb * 64 + j * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xv[j] = has_x ? *reinterpret_cast<const u32x4*>(xp + kb * 64 + j * 8) : zero;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[j]);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa[j]), xf, acc0, 0, 0, 0);
+            if constexpr (EPI == EPI_SWIGLU)
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wb[j]), xf, acc1, 0, 0, 0);
+        }
+    }
+    // reduce the K-slices: thread (rp, lane) owns accumulators 2 rp, 2 rp + 1 = two adjacent columns of token l32
+    const int rp = wave;
+    float v0[2] = {0.f, 0.f}, v1[2] = {0.f, 0.f};
+    for (int pass = 0; pass < (EPI == EPI_SWIGLU ? 2 : 1); ++pass) {
+        if (pass) __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) part[wave][r][lane] = pass ? acc1[r] : acc0[r];
+        __syncthreads();
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) { s0 += part[w][2 * rp][lane]; s1 += part[w][2 * rp + 1][lane]; }
+        if (pass) { v1[0] = s0; v1[1] = s1; } else { v0[0] = s0; v0[1] = s1; }
+    }
+    if (!has_x) return;
+    const int m = l32;
+    // accumulator r of a lane is column (r / 4) * 8 + lh * 4 + r % 4 of the block
+    const int col = ((2 * rp) / 4) * 8 + lh * 4 + (2 * rp) % 4;
+    const int n = n_blk + col;
+    if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
+        float* dst = g.Cf + (int64_t)m * g.N + n;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v0[e] : v0[e];
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        const int f = g.N / 2;
+        bf16* dst = g.Cb + (int64_t)m * f + n;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
+    } else if constexpr (EPI == EPI_QK) {
+        const int seg = n / g.d, c = n - seg * g.d;
+        const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
+        const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
+        const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
+        bf16* dst;
+        if (seg == 0) {
+            dst = g.Cb + (((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc;
+        } else {
+            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+            dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
+        }
+        dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
+        dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
+    } else {   // EPI_V: transposed cache
+        const int dh = g.ra.head_dim;
+        const int b = m / g.ra.L, jj = m % g.ra.L;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int hd = (n + e) / dh, cc = (n + e) % dh;
+            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+            if (n + e < g.N) g.vc[(hb * dh + cc) * g.ra.max_seq + g.ra.P + jj] = __float2bfloat16(v0[e]);
+        }
+    }
+}
+
+template <int EPI>
+void run_gemv(const GemmArgs& g, hipStream_t st) {
+    const int cols = EPI == EPI_SWIGLU ? g.N / 2 : g.N;
+    hipLaunchKernelGGL(k_gemv_bf16<EPI>, dim3((cols + 31) / 32), dim3(512), 0, st, g);
+}
+
 template <int EPI>
 void dispatch(const GemmArgs& g, hipStream_t st) {
+    if (g.M <= 32 && (EPI != EPI_QK || g.d % 32 == 0)) {   // a handful of tokens: stream the weights
+        run_gemv<EPI>(g, st);
+        return;
+    }
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
     const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
