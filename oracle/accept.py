@@ -27,6 +27,15 @@ from .upsample import softmax_rows
 NEAR_TIE = 1e-4
 
 
+def guided_logits(z_cond, z_uncond, scale):
+    """Classifier-free guidance (supplement, "Sampling": scale 4.0, empty negative prompt).  The paper names
+    the technique and the scale, not the formula; the standard one is taken:
+    z = z_u + s (z_c - z_u), in float64 (s = 1 gives the conditional logits, s = 0 the unconditional)."""
+    zc = np.asarray(z_cond, dtype=np.float64)
+    zu = np.asarray(z_uncond, dtype=np.float64)
+    return zu + float(scale) * (zc - zu)
+
+
 def target_probs(logits):
     """p = softmax(logits) over the last axis: float64 inside, rounded once to float32."""
     return softmax_rows(logits).astype(np.float32)

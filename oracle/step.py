@@ -12,11 +12,14 @@ from . import upsample as UP
 
 
 def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1,
-           seed=0, rng_counter=0, nbr=None, mode=0, accept_mode=0, tau=0.0):
+           seed=0, rng_counter=0, nbr=None, mode=0, accept_mode=0, tau=0.0, logits_uncond=None,
+           cfg_scale=1.0):
     """Decision stage on given logits (Sec. 3.1 Eq. 1-3, Sec. 3.3 Eq. 5-7).
 
     accept_mode 0: speculative test u q < pbar (Eq. 1 / Eq. 3); accept_mode 1:
     threshold test pbar >= tau (Eq. 5), where q_rows may be None if mode == 2.
+    logits_uncond: float [B, L, V] or None; with it the target distribution is the softmax of the
+    guided logits z_u + cfg_scale (z_c - z_u) (classifier-free guidance, supplement "Sampling").
 
     logits: float [B, L, V]; q_rows: float32 [B, n_q, V]; q_row_index: int [L]
     or None (identity); draft_tokens: int [B, L].
@@ -24,6 +27,8 @@ def decide(logits, q_rows, q_row_index, draft_tokens, *, W, n0, radius, expand=1
     tokens_out, stats [B, 4] = (accepted, rejected, marked, near ties).
     """
     logits = np.asarray(logits)
+    if logits_uncond is not None:
+        logits = A.guided_logits(logits, logits_uncond, cfg_scale)
     B, L, V = logits.shape
     qi = np.arange(L) if q_row_index is None else np.asarray(q_row_index).astype(np.int64)
     toks = np.asarray(draft_tokens).astype(np.int64).reshape(B, L)

@@ -513,3 +513,32 @@ def test_tau_rule_pooled_mass_with_neighbour_table():
             assert bool(out["accept"][0, t]) == (want >= 0.2)
     one = ST.decide(z, None, None, toks, W=4, n0=0, radius=1, accept_mode=1, tau=0.2, mode=2)
     assert (out["accept"] >= one["accept"]).all()      # pooling can only add mass
+
+
+# ------------------------------------------------------------------ classifier-free guidance
+def test_guidance_special_scales_closed_form_and_effect_on_decisions():
+    rng = np.random.default_rng(17)
+    B, L, V = 1, 16, 12
+    zc = rng.normal(0, 1.5, (B, L, V)).astype(np.float32)
+    zu = rng.normal(0, 1.5, (B, L, V)).astype(np.float32)
+    toks = rng.integers(0, V, (B, L))
+    kw = dict(W=4, n0=0, radius=1, accept_mode=1, tau=0.05, mode=2, seed=2)
+    base_c = ST.decide(zc, None, None, toks, **kw)
+    base_u = ST.decide(zu, None, None, toks, **kw)
+    s1 = ST.decide(zc, None, None, toks, logits_uncond=zu, cfg_scale=1.0, **kw)
+    s0 = ST.decide(zc, None, None, toks, logits_uncond=zu, cfg_scale=0.0, **kw)
+    assert np.array_equal(s1["p"], base_c["p"]) and np.array_equal(s1["tokens_out"], base_c["tokens_out"])   # s = 1: conditional
+    assert np.array_equal(s0["p"], base_u["p"]) and np.array_equal(s0["accept"], base_u["accept"])           # s = 0: unconditional
+    same = ST.decide(zc, None, None, toks, logits_uncond=zc, cfg_scale=4.0, **kw)                            # z_c = z_u: no effect at any scale
+    assert np.allclose(same["p"], base_c["p"], atol=1e-7)
+    # closed form: guided p is proportional to p_c^s p_u^(1-s)
+    g = ST.decide(zc, None, None, toks, logits_uncond=zu, cfg_scale=4.0, **kw)
+    pc = scipy.special.softmax(zc.astype(np.float64), -1); pu = scipy.special.softmax(zu.astype(np.float64), -1)
+    ref = pc ** 4.0 * pu ** -3.0
+    ref /= ref.sum(-1, keepdims=True)
+    assert np.abs(g["p"] - ref).max() < 1e-6
+    # a two-entry hand example: z_c = (0, ln 3), z_u = (0, 0), s = 2 -> z = (0, 2 ln 3) -> p = (1/10, 9/10)
+    h = ST.decide(np.array([[[0.0, np.log(3.0)]]], np.float32), None, None, np.array([[1]]), W=1, n0=0, radius=0,
+                  accept_mode=1, tau=0.5, mode=2, logits_uncond=np.zeros((1, 1, 2), np.float32), cfg_scale=2.0)
+    assert np.allclose(h["p"][0, 0], [0.1, 0.9], atol=1e-6) and h["accept"][0, 0] == 1
+    assert not np.array_equal(g["accept"], base_c["accept"]) or not np.array_equal(g["tokens_out"], base_c["tokens_out"])
