@@ -111,6 +111,11 @@ typedef enum { MULO_ACCEPT_RATIO = 0, MULO_ACCEPT_TAU = 1 } mulo_accept_mode;
  *               pbar >= tau (float32), no draft probability and no uniform;
  *               with resample_mode 2 the draft distribution is not read at all
  *   tau         threshold of Eq. 5, finite and >= 0 (read in MULO_ACCEPT_TAU only)
+ *   cfg_scale   0: off.  s > 0: classifier-free guidance (supplement, "Sampling": s = 4, empty negative
+ *               prompt); the target distribution is softmax(z_u + s (z_c - z_u)).  The entry points
+ *               then work on 2 B sequences: sequence b is the conditional one, B + b its
+ *               unconditional twin (own cache rows, same image tokens, prefix of the same length P);
+ *               logits arguments are [2 B, L, vocab] and 2 B <= max_batch
  *   seed, rng_counter  Philox4x32-10 key and per-step counter; position t of
  *               batch element b uses counter words (t, b, counter_lo,
  *               stream << 24 | counter_hi & 0xffffff), stream 0 for the accept
@@ -124,6 +129,7 @@ typedef struct {
     uint64_t seed, rng_counter;
     int32_t accept_mode;
     float tau;
+    float cfg_scale;
 } mulo_step_params;
 
 /* Static description of a status code; never NULL. */
@@ -200,7 +206,8 @@ MULO_API mulo_status mulo_accept_local_resample(mulo_ctx *ctx, int32_t B, const 
  *   draft        device float32 [B, h_blk*w, vocab] logits (or probabilities); may be
  *                NULL when accept_mode is MULO_ACCEPT_TAU and resample_mode is 2
  *   draft_tokens device int32 [B, h_blk*w]
- *   prev_tokens  device int32 [B]  last committed (or last prefix) token
+ *   prev_tokens  device int32 [B]  last committed (or last prefix) token (with guidance: also fed
+ *                to the unconditional twin)
  *   tokens_hi    device int32 [B, L] (out) or NULL: the up-sampled draft x~
  *   logits       device float32 [B, L, vocab] (out) or NULL
  *   other outputs as in mulo_accept_local_resample. */

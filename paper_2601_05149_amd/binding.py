@@ -46,7 +46,7 @@ class StepParams(C.Structure):
                 ("radius", C.c_int32), ("expand", C.c_int32), ("pool_k", C.c_int32),
                 ("nbr", C.c_void_p), ("resample_mode", C.c_int32),
                 ("seed", C.c_uint64), ("rng_counter", C.c_uint64),
-                ("accept_mode", C.c_int32), ("tau", C.c_float)]
+                ("accept_mode", C.c_int32), ("tau", C.c_float), ("cfg_scale", C.c_float)]
 
 
 _lib = None
@@ -117,9 +117,9 @@ MULO_ACCEPT_RATIO, MULO_ACCEPT_TAU = 0, 1
 
 
 def make_params(H, W, n0, L, radius, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0, rng_counter=0,
-                accept_mode=MULO_ACCEPT_RATIO, tau=0.0):
+                accept_mode=MULO_ACCEPT_RATIO, tau=0.0, cfg_scale=0.0):
     return StepParams(H, W, n0, L, radius, expand, pool_k, _ptr(nbr, torch.int32, True), resample_mode,
-                      seed, rng_counter, accept_mode, tau)
+                      seed, rng_counter, accept_mode, tau, cfg_scale)
 
 
 class Ctx:

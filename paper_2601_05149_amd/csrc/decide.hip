@@ -76,6 +76,24 @@ __device__ __forceinline__ float prob(float z, float m, float inv) {
     return __fmul_rn(expm(z, m), inv);
 }
 
+// Classifier-free guidance of a target logit: z_u + s (z_c - z_u), every operation rounded on its own so
+// that all kernels reproduce the same bits; zu == nullptr (no guidance) returns the logit unchanged.
+__device__ __forceinline__ float guide(float zc, float zu, float s) {
+    return __fadd_rn(zu, __fmul_rn(s, __fsub_rn(zc, zu)));
+}
+struct Guided {
+    const float* zc;   // row of conditional logits
+    const float* zu;   // row of unconditional logits or nullptr
+    float s;
+    __device__ __forceinline__ float at(int i) const { return zu ? guide(zc[i], zu[i], s) : zc[i]; }
+    __device__ __forceinline__ float4 at4(int i4) const {
+        const float4 c = reinterpret_cast<const float4*>(zc)[i4];
+        if (!zu) return c;
+        const float4 u = reinterpret_cast<const float4*>(zu)[i4];
+        return make_float4(guide(c.x, u.x, s), guide(c.y, u.y, s), guide(c.z, u.z, s), guide(c.w, u.w, s));
+    }
+};
+
 // Philox4x32-10 (Salmon et al., SC'11), word 0 of the output block.
 __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                  uint32_t k0, uint32_t k1) {
@@ -99,22 +117,21 @@ struct RowRegs {
 };
 
 template <int NV4>
-__device__ __forceinline__ void row_stats(const float* __restrict__ src, int V, RowRegs<NV4>& rr,
+__device__ __forceinline__ void row_stats(const Guided src, int V, RowRegs<NV4>& rr,
                                           float* red, float& m, float& inv) {
     const int nv4 = V >> 2, tid = threadIdx.x;
-    const float4* s4 = reinterpret_cast<const float4*>(src);
     const float NEG = -__builtin_huge_valf();
     float mx = NEG;
     if constexpr (NV4 > 0) {
 #pragma unroll
         for (int i = 0; i < NV4; ++i) {
             const int idx = i * TPB + tid;
-            rr.v[i] = idx < nv4 ? s4[idx] : make_float4(NEG, NEG, NEG, NEG);
+            rr.v[i] = idx < nv4 ? src.at4(idx) : make_float4(NEG, NEG, NEG, NEG);
             mx = fmaxf(fmaxf(mx, fmaxf(rr.v[i].x, rr.v[i].y)), fmaxf(rr.v[i].z, rr.v[i].w));
         }
     } else {
         for (int idx = tid; idx < nv4; idx += TPB) {
-            const float4 t = s4[idx];
+            const float4 t = src.at4(idx);
             mx = fmaxf(fmaxf(mx, fmaxf(t.x, t.y)), fmaxf(t.z, t.w));
         }
     }
@@ -129,7 +146,7 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ src, int V, 
         }
     } else {
         for (int idx = tid; idx < nv4; idx += TPB) {
-            const float4 t = s4[idx];
+            const float4 t = src.at4(idx);
             s += (expm(t.x, m) + expm(t.y, m)) + (expm(t.z, m) + expm(t.w, m));
         }
     }
@@ -138,7 +155,7 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ src, int V, 
 }
 
 template <int NV4>
-__device__ __forceinline__ void row_write_probs(const float* __restrict__ src, float* __restrict__ dst,
+__device__ __forceinline__ void row_write_probs(const Guided src, float* __restrict__ dst,
                                                 int V, const RowRegs<NV4>& rr, float m, float inv) {
     const int nv4 = V >> 2, tid = threadIdx.x;
     float4* d4 = reinterpret_cast<float4*>(dst);
@@ -151,9 +168,8 @@ __device__ __forceinline__ void row_write_probs(const float* __restrict__ src, f
                                       __fmul_rn(rr.v[i].z, inv), __fmul_rn(rr.v[i].w, inv));
         }
     } else {
-        const float4* s4 = reinterpret_cast<const float4*>(src);
         for (int idx = tid; idx < nv4; idx += TPB) {
-            const float4 t = s4[idx];
+            const float4 t = src.at4(idx);
             d4[idx] = make_float4(prob(t.x, m, inv), prob(t.y, m, inv), prob(t.z, m, inv),
                                   prob(t.w, m, inv));
         }
@@ -168,8 +184,9 @@ __global__ __launch_bounds__(TPB) void k_softmax_rows(const float* __restrict__ 
     const int64_t row = blockIdx.x;
     RowRegs<NV4> rr;
     float m, inv;
-    row_stats<NV4>(in + row * V, V, rr, red, m, inv);
-    row_write_probs<NV4>(in + row * V, out + row * V, V, rr, m, inv);
+    const Guided src{in + row * V, nullptr, 1.f};
+    row_stats<NV4>(src, V, rr, red, m, inv);
+    row_write_probs<NV4>(src, out + row * V, V, rr, m, inv);
 }
 
 __global__ __launch_bounds__(TPB) void k_copy(const float4* __restrict__ in, float4* __restrict__ out,
@@ -225,7 +242,7 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
     __shared__ float red[WAVES];
     const int64_t row = blockIdx.x;
     const int b = row / a.L, t = row % a.L, tid = threadIdx.x;
-    const float* z = a.logits + row * a.V;
+    const Guided z{a.logits + row * a.V, a.logits_u ? a.logits_u + row * a.V : nullptr, a.cfg_scale};
     // the scalar gathers (draft token -> its logit and its draft probability) are issued first, so that
     // their chained latency is hidden behind the streaming of the row
     const int tok = clamp_tok(a.draft_tokens[row], a.V);
@@ -235,7 +252,7 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
             const int qr = a.q_row ? a.q_row[t] : t;
             qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
         }
-        ztok = z[tok];
+        ztok = z.at(tok);
     }
     RowRegs<NV4> rr;
     float m, inv;
@@ -248,7 +265,7 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
     } else {  // Eq. 3: pooled mass over the codebook neighbours of the draft token
         float acc = 0.f;
         for (int i = tid; i < a.pool_k; i += TPB)
-            acc += prob(z[clamp_tok(a.nbr[(int64_t)tok * a.pool_k + i], a.V)], m, inv);
+            acc += prob(z.at(clamp_tok(a.nbr[(int64_t)tok * a.pool_k + i], a.V)), m, inv);
         pbar = block_sum(acc, red);
     }
     if (tid == 0) {
@@ -284,7 +301,7 @@ __device__ __forceinline__ void weights4(const float4 z, const float4 qv, float 
 // Integer-CDF draw of one row by one workgroup: W(x) = floor(w(x) 2^40) with w = max(0, p - q) (or p when
 // use_p), T = (word * tot) >> 32, token = first x whose inclusive prefix exceeds T; an empty residual falls
 // back to p.  The token is stored to *out by the lane that finds it.
-__device__ __forceinline__ void cdf_draw(const float4* __restrict__ z4, const float4* __restrict__ q4, float m,
+__device__ __forceinline__ void cdf_draw(const Guided z, const float4* __restrict__ q4, float m,
                                          float inv, bool use_p, uint32_t word, int V, int fallback_tok,
                                          int32_t* out, unsigned long long* chunk, int* s_retry) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -296,7 +313,7 @@ __device__ __forceinline__ void cdf_draw(const float4* __restrict__ z4, const fl
             unsigned long long s = 0;
             if (idx < nv4) {
                 unsigned long long w[4];
-                weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                weights4(z.at4(idx), use_p ? zero4 : q4[idx], m, inv, use_p, w);
                 s = (w[0] + w[1]) + (w[2] + w[3]);
             }
             s = wave_sum_u64(s);
@@ -330,7 +347,7 @@ __device__ __forceinline__ void cdf_draw(const float4* __restrict__ z4, const fl
                 // inside the chunk: 64 lanes x 4 entries, same weights as above
                 const int idx = cidx * 64 + lane;
                 unsigned long long w[4] = {0, 0, 0, 0};
-                if (idx < nv4) weights4(z4[idx], use_p ? zero4 : q4[idx], m, inv, use_p, w);
+                if (idx < nv4) weights4(z.at4(idx), use_p ? zero4 : q4[idx], m, inv, use_p, w);
                 const unsigned long long s = (w[0] + w[1]) + (w[2] + w[3]);
                 const unsigned long long incl = wave_scan_u64(s, lane) + before;
                 const unsigned long long hit = __ballot(incl > T);
@@ -389,14 +406,14 @@ __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
 
     // Residual draw through the integer CDF
     const int V = a.V;
-    const float4* z4 = reinterpret_cast<const float4*>(a.logits + row * V);
+    const Guided z{a.logits + row * V, a.logits_u ? a.logits_u + row * V : nullptr, a.cfg_scale};
     const int qr = a.q_row ? a.q_row[t] : t;
     const bool use_p = a.resample_mode == 2 || ((a.resample_mode == 1) && a.accept[row] != 0);
     // the draft row is read only for residual weights (it may be absent when every draw is from p)
-    const float4* q4 = a.q ? reinterpret_cast<const float4*>(a.q + b * a.q_batch_stride + (int64_t)qr * V) : z4;
+    const float4* q4 = reinterpret_cast<const float4*>(a.q ? a.q + b * a.q_batch_stride + (int64_t)qr * V : z.zc);
     const uint32_t word = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24 | (1u << 24),
                                        a.key0, a.key1);
-    cdf_draw(z4, q4, a.rowmax[row], a.rowinv[row], use_p, word, V, draft, &a.tokens_out[row], chunk, &s_retry);
+    cdf_draw(z, q4, a.rowmax[row], a.rowinv[row], use_p, word, V, draft, &a.tokens_out[row], chunk, &s_retry);
 }
 
 // ---- Alg. 1 Step 6, one position: inputs of the single-token forward, then the draw from p ----
@@ -415,14 +432,13 @@ __global__ __launch_bounds__(TPB) void k_seq_draw(const float* __restrict__ logi
     __shared__ float red[WAVES];
     const int b = blockIdx.x;
     if (!mask[(int64_t)b * L + u]) return;   // uniform over the workgroup
-    const float* z = logits + (int64_t)b * V;
+    const Guided z{logits + (int64_t)b * V, nullptr, 1.f};
     RowRegs<0> none;
     float m, inv;
     row_stats<0>(z, V, none, red, m, inv);
     const uint32_t word = philox_word0((uint32_t)u, (uint32_t)b, ctr_lo, ctr_hi24 | (2u << 24), key0, key1);
-    const float4* z4 = reinterpret_cast<const float4*>(z);
     int32_t* out = tokens + (int64_t)b * L + u;
-    cdf_draw(z4, z4, m, inv, true, word, V, *out, out, chunk, &s_retry);
+    cdf_draw(z, reinterpret_cast<const float4*>(z.zc), m, inv, true, word, V, *out, out, chunk, &s_retry);
 }
 
 template <int NV4>

@@ -176,6 +176,7 @@ void fill_decide(DecideArgs& a, const mulo_ctx* ctx, int B, const mulo_step_para
     a.resample_mode = p->resample_mode;
     a.accept_mode = p->accept_mode;
     a.tau = p->tau;
+    a.cfg_scale = p->cfg_scale;
     a.key0 = (uint32_t)(p->seed & 0xFFFFFFFFu);
     a.key1 = (uint32_t)(p->seed >> 32);
     a.ctr_lo = (uint32_t)(p->rng_counter & 0xFFFFFFFFu);
@@ -226,10 +227,11 @@ mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mul
     if (B < 1 || p->H < 1 || p->W < 1 || p->L < 1 || p->n0 < 0 || p->radius < -1 || p->expand < 0 ||
         p->pool_k < 1 || p->resample_mode < 0 || p->resample_mode > 2 ||
         (p->accept_mode != MULO_ACCEPT_RATIO && p->accept_mode != MULO_ACCEPT_TAU) ||
-        (p->accept_mode == MULO_ACCEPT_TAU && !(p->tau >= 0.f && p->tau <= 3.0e38f)))
+        (p->accept_mode == MULO_ACCEPT_TAU && !(p->tau >= 0.f && p->tau <= 3.0e38f)) ||
+        !(p->cfg_scale >= 0.f && p->cfg_scale <= 1.0e6f))
         return MULO_ERR_RANGE;
     if ((int64_t)p->radius * p->expand > 4096) return MULO_ERR_RANGE;
-    if (B > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
+    if ((p->cfg_scale > 0.f ? 2 * (int64_t)B : (int64_t)B) > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
     if (p->L % p->W || p->n0 % p->W || (int64_t)p->n0 + p->L > (int64_t)p->H * p->W) return MULO_ERR_SHAPE;
     if (p->pool_k > 1 && !p->nbr) return MULO_ERR_NULL;
     if (p->pool_k > c->vocab) return MULO_ERR_RANGE;
@@ -348,6 +350,7 @@ mulo_status mulo_accept_local_resample(mulo_ctx* ctx, int32_t B, const mulo_step
     DecideArgs a{};
     fill_decide(a, ctx, B, p);
     a.logits = logits; a.q = q; a.q_row = q_row; a.q_batch_stride = q_batch_stride;
+    a.logits_u = p->cfg_scale > 0.f ? logits + (int64_t)B * p->L * ctx->cfg.vocab : nullptr;
     a.draft_tokens = draft_tokens; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = p_probs;
     enqueue_decide(ctx, a);
@@ -367,7 +370,9 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     if (need_q && !draft) return MULO_ERR_NULL;
     if (h_blk < 1 || w < 1 || r < 1) return MULO_ERR_RANGE;
     if ((int64_t)h_blk * r * w * r != p->L || w * r != p->W) return MULO_ERR_SHAPE;
-    s = check_forward_args(ctx, kv, B, p->L, P);
+    const bool cfg_on = p->cfg_scale > 0.f;
+    const int B2 = cfg_on ? 2 * B : B;      // guidance: the unconditional twins are sequences B .. 2B-1
+    s = check_forward_args(ctx, kv, B2, p->L, P);
     if (s != MULO_OK) return s;
 
     const int L = p->L, V = ctx->cfg.vocab, n_lo = h_blk * w;
@@ -378,12 +383,14 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     enqueue_upsample(ctx, B, h_blk, w, r, need_q ? draft : nullptr, input_is_probs, draft_tokens, thi, ctx->q_lo,
                      ctx->q_row, nullptr);
     // Step 3: inputs [prev, x~_0 .. x~_{L-2}] so that logit row j is p of draft position j
-    { mulo_ctx* c = ctx; PROF(MULO_PROF_OTHER); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st); }
-    enqueue_forward(ctx, kv, B, L, P, ctx->inputs, nullptr, lg);
+    { mulo_ctx* c = ctx; PROF(MULO_PROF_OTHER); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st);
+      if (cfg_on) launch_shift_inputs(prev_tokens, thi, ctx->inputs + (int64_t)B * L, B, L, st); }
+    enqueue_forward(ctx, kv, B2, L, P, ctx->inputs, nullptr, lg);
     // Steps 4-5 + residual re-draw
     DecideArgs a{};
     fill_decide(a, ctx, B, p);
     a.logits = lg; a.q = need_q ? ctx->q_lo : nullptr; a.q_row = ctx->q_row; a.q_batch_stride = (int64_t)n_lo * V;
+    a.logits_u = cfg_on ? lg + (int64_t)B * L * V : nullptr;
     a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = nullptr;
     enqueue_decide(ctx, a);

@@ -19,6 +19,8 @@ struct DecideArgs {
     float tau;
     uint32_t key0, key1, ctr_lo, ctr_hi24;
     const float* logits;        // [B, L, V]
+    const float* logits_u;      // [B, L, V] unconditional logits (classifier-free guidance) or nullptr
+    float cfg_scale;
     const float* q;             // rows of V floats
     const int32_t* q_row;       // [L] or nullptr
     int64_t q_batch_stride;

@@ -297,3 +297,38 @@ def test_sampler_words_equal_the_oracle_generator_on_2_pow_20_counters():
         n_bad += int((got != (words >> 16).astype(np.int64)).sum())
     say("  sampler words: %d of %d positions differ" % (n_bad, 256 * B * L))
     assert n_bad == 0
+
+
+# --------------------------------------------------------------- classifier-free guidance
+@pytest.mark.parametrize("B,V,scale,amode", [(2, 1024, 4.0, 1), (1, 16384, 4.0, 0), (2, 20000, 1.5, 1), (2, 2048, 1.0, 0)])
+def test_guided_decide_parity(B, V, scale, amode):
+    say("guided decide B=%d V=%d s=%g accept_mode=%d" % (B, V, scale, amode))
+    H, W, L = 8, 8, 64
+    ctx = decide_ctx(V, 4, 1024)
+    zc, q, toks = clean_inputs(B, L, V, 1.0, seed=8)
+    zu = 0.7 * zc + 0.5 * G.normal_logits((B, L, V), 1.0, 8, tag=99)       # correlated with the conditional logits
+    kw = dict(W=W, n0=0, radius=1, expand=1, seed=13, rng_counter=21)
+    mode = 2 if amode == 1 else 0
+    ref = ST.decide(zc, q, None, toks, mode=mode, accept_mode=amode, tau=2e-3, logits_uncond=zu, cfg_scale=scale, **kw)
+    z2 = np.ascontiguousarray(np.concatenate([zc, zu], axis=0))           # [2B, L, V]: conditional, then unconditional
+    params = mulo.make_params(H, W, 0, L, 1, 1, resample_mode=mode, seed=13, rng_counter=21, accept_mode=amode, tau=2e-3,
+                              cfg_scale=scale)
+    out = decide_buffers(B, L)
+    pp = torch.empty(B, L, V, device=DEV)
+    mulo.mulo_accept_local_resample(ctx, B, params, dev(z2, torch.float32), dev(q, torch.float32), None, L * V,
+                                    dev(toks, torch.int32), out["tokens_out"], out["accept"], out["mask"], out["t0"],
+                                    out["stats"], pp)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    got["p"] = pp.cpu().numpy()
+    perr = np.abs(got["p"] - ref["p"]).max()
+    rep = compare_decisions(got, ref, toks, q, None, mode=mode, label="guided")
+    say("  acc rate %.3f marked %.3f | max|p err| %.3g | %r" % (ref["accept"].mean(), ref["mask"].mean(), perr, rep))
+    assert perr <= 1e-5 and rep["sequences_checked"] >= 1
+    if scale == 1.0:      # s = 1 is the conditional distribution: same decisions as without guidance
+        plain = run_decide(ctx, zc, q, toks, H=H, L=L, resample_mode=mode, accept_mode=amode, tau=2e-3, **kw)
+        assert np.array_equal(plain["accept"], got["accept"]) and np.array_equal(plain["tokens_out"], got["tokens_out"])
+    with pytest.raises(mulo.MuloError):        # 2 B sequences must fit the context
+        mulo.mulo_accept_local_resample(ctx, 3, params, dev(z2, torch.float32), dev(q, torch.float32), None, L * V,
+                                        dev(toks, torch.int32), out["tokens_out"], out["accept"], out["mask"], out["t0"],
+                                        out["stats"], None)

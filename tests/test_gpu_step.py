@@ -244,3 +244,49 @@ def test_step_tau_rule_without_draft_distribution_vs_oracle():
                               torch.tensor(np.ascontiguousarray(prefix[:, -1]), device=DEV), out["tokens_out"],
                               out["accept"], out["mask"], out["t0"], out["stats"], None, None)
     assert e.value.status == 1
+
+
+def test_step_with_guidance_equals_its_composition_on_device():
+    """Classifier-free guidance through the whole step: the forward runs on 2 B sequences (conditional and
+    unconditional caches), the decision stage guides the logits.  The step must equal forward(2B) + decide."""
+    c = WC.get("cfg1")
+    m, B, L, Pn, V = c["model"], c["B"], c["L"], c["prefix"], c["model"]["vocab"]
+    w = G.make_weights(m, seed=0)
+    ctx, cos, sin = make_ctx(m, w, 2 * B, c["max_seq"], L)
+    kv = mulo.alloc_kv(ctx, DEV)
+    prefix = np.concatenate([G.uniform_tokens((B, Pn), V, 0, tag=0), G.uniform_tokens((B, Pn), V, 0, tag=7)], axis=0)   # cond, uncond
+    mulo.mulo_verify_forward(ctx, kv, 2 * B, Pn, 0, torch.tensor(prefix, device=DEV), None, torch.empty(2 * B, Pn, V, device=DEV))
+    dl = G.normal_logits((B, c["h"] * c["w"], V), c["draft_std"], 0, tag=0)
+    dt = G.sample_categorical(dl, 0, tag=0)
+    prev = torch.tensor(np.ascontiguousarray(prefix[:B, -1]), device=DEV)
+    params = mulo.make_params(c["H"], c["W"], 0, L, c["radius"], c["expand"], seed=0, rng_counter=5, cfg_scale=4.0)
+    out = decide_buffers(B, L)
+    thi = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    lg = torch.empty(2 * B, L, V, device=DEV)
+    mulo.mulo_verify_step(ctx, kv, B, Pn, params, c["h"], c["w"], c["r"], torch.tensor(dl, device=DEV), 0,
+                          torch.tensor(dt, device=DEV), prev, out["tokens_out"], out["accept"], out["mask"], out["t0"],
+                          out["stats"], thi, lg)
+    # composition
+    q_lo = torch.empty(B, c["h"] * c["w"], V, device=DEV)
+    q_row = torch.empty(L, dtype=torch.int32, device=DEV)
+    thi2 = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    mulo.mulo_upsample_draft(ctx, B, c["h"], c["w"], c["r"], torch.tensor(dl, device=DEV), 0, torch.tensor(dt, device=DEV), thi2, q_lo, q_row, None)
+    inp = torch.cat([prev.reshape(B, 1), thi2[:, :L - 1]], dim=1)
+    inp2 = torch.cat([inp, inp], dim=0).contiguous()
+    lg2 = torch.empty(2 * B, L, V, device=DEV)
+    mulo.mulo_verify_forward(ctx, kv, 2 * B, L, Pn, inp2, None, lg2)
+    out2 = decide_buffers(B, L)
+    mulo.mulo_accept_local_resample(ctx, B, params, lg2, q_lo, q_row, c["h"] * c["w"] * V, thi2, out2["tokens_out"],
+                                    out2["accept"], out2["mask"], out2["t0"], out2["stats"], None)
+    torch.cuda.synchronize()
+    assert torch.equal(lg, lg2) and torch.equal(thi, thi2)
+    for k in ("tokens_out", "accept", "mask", "t0", "stats"):
+        assert torch.equal(out[k], out2[k]), k
+    # and against the oracle's decision stage on the device's own logits
+    z = lg.cpu().numpy()
+    ref = ST.decide(z[:B], q_lo.cpu().numpy(), q_row.cpu().numpy(), thi.cpu().numpy(), W=c["W"], n0=0, radius=c["radius"],
+                    expand=c["expand"], seed=0, rng_counter=5, logits_uncond=z[B:], cfg_scale=4.0)
+    from tests.gpu_util import compare_decisions
+    rep = compare_decisions(to_np(out), ref, thi.cpu().numpy(), q_lo.cpu().numpy(), q_row.cpu().numpy(), label="guided step")
+    say("  guided step: acc %.3f marked %.3f %r" % (ref["accept"].mean(), ref["mask"].mean(), rep))
+    assert not np.array_equal(z[:B], z[B:])
