@@ -34,7 +34,10 @@ struct AttnArgs {
     bf16* out;        // [B*L, nh*dh]
     int B, L, P, nh, max_seq, max_batch, layer;
     float scale_log2;  // log2(e) / sqrt(dh)
+    int nsplit;        // > 1: the keys are dealt to nsplit workgroups per (sequence, head); one query tile only
+    float* part;       // [nsplit, B, nh][dh + 2]: unnormalised output of the single query, running maximum, running sum
 };
+constexpr int MAX_SPLIT = 16;
 
 template <int DH>
 __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
@@ -54,14 +57,15 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     // order, so that they stream that head's K and V through the same L2 side by side (the cache rows
     // are fetched from memory once per head instead of once per query tile).  Long tiles go first.
     const int qtiles = (a.L + BQ - 1) / BQ, nbh = a.B * a.nh;
+    const int split = blockIdx.x / (qtiles * nbh), bid = blockIdx.x % (qtiles * nbh);
     int qt, bh;
     if ((nbh & 7) == 0) {
-        const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+        const int xcd = bid & 7, s = bid >> 3;
         qt = qtiles - 1 - s % qtiles;
         bh = (s / qtiles) * 8 + xcd;
     } else {
-        qt = qtiles - 1 - blockIdx.x % qtiles;
-        bh = blockIdx.x / qtiles;
+        qt = qtiles - 1 - bid % qtiles;
+        bh = bid / qtiles;
     }
     const int j0 = qt * BQ, hd = bh % a.nh, b = bh / a.nh;
     const int64_t hb = ((int64_t)a.layer * a.max_batch + b) * a.nh + hd;
@@ -88,6 +92,18 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     blk_jmax = blk_jmax < a.L ? blk_jmax : a.L - 1;
     const int kmax_blk = a.P + blk_jmax;   // last key any query of this workgroup may see
     const int n_tiles = kmax_blk / BKV + 1;
+    // key split (single-token decoding): this workgroup covers tiles [t_begin, t_end) and leaves its
+    // unnormalised partial result (output, running maximum, running sum) for k_attn_combine
+    const int tiles_per = (n_tiles + a.nsplit - 1) / a.nsplit;
+    const int t_begin = split * tiles_per, t_end = t_begin + tiles_per < n_tiles ? t_begin + tiles_per : n_tiles;
+    float* part = a.nsplit > 1 ? a.part + (((int64_t)split * a.B + b) * a.nh + hd) * (DH + 2) : nullptr;
+    if (t_begin >= t_end) {    // uniform over the workgroup, before any barrier: an empty share
+        if (part) {
+            for (int c = tid; c < DH; c += NTH) part[c] = 0.f;
+            if (tid == 0) { part[DH] = -__builtin_huge_valf(); part[DH + 1] = 0.f; }
+        }
+        return;
+    }
 
     u32x4 rk[LK], rv[LV];
     auto gload = [&](int t) {
@@ -141,12 +157,12 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     // MFMA row rho of a K block is fed key kperm(rho): bits 2 and 3 swapped
     const int kperm = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
 
-    gload(0);
-    sstore(0);
+    gload(t_begin);
+    sstore(t_begin & 1);
     __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
+    for (int t = t_begin; t < t_end; ++t) {
         const int kv0 = t * BKV;
-        const int t_next = t + 1 < n_tiles ? t + 1 : t;   // the last tile is fetched twice: no branch in the body
+        const int t_next = t + 1 < t_end ? t + 1 : t;   // the last tile is fetched twice: no branch in the body
         if (wave_live && kv0 <= a.P + wave_jmax) {
             gload(t_next);
             const bf16* k = sK + (t & 1) * BKV * KS;
@@ -219,6 +235,16 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
     }
 
     l_run += __shfl_xor(l_run, 32);
+    if (part) {
+        if (wave == 0 && l32 == 0) {     // the single query of the tile
+#pragma unroll
+            for (int i = 0; i < NDB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3)] = o[i][r];
+            if (lh == 0) { part[DH] = m_run; part[DH + 1] = l_run; }
+        }
+        return;
+    }
     if (jq_raw < a.L) {
         const float inv = 1.0f / l_run;
         bf16* op = a.out + ((int64_t)b * a.L + jq) * (a.nh * DH) + hd * DH;
@@ -280,6 +306,22 @@ __global__ __launch_bounds__(256) void k_attn_f32(const float* __restrict__ q, c
     }
 }
 
+// out[b, hd, :] = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s (maxima are in exponent units)
+template <int DH>
+__global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
+    const int hd = blockIdx.x % a.nh, b = blockIdx.x / a.nh, c = threadIdx.x;
+    float M = -__builtin_huge_valf();
+    for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.B + b) * a.nh + hd) * (DH + 2) + DH]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < a.nsplit; ++s) {
+        const float* p = a.part + (((int64_t)s * a.B + b) * a.nh + hd) * (DH + 2);
+        const float wgt = __builtin_amdgcn_exp2f(p[DH] - M);
+        num += p[c] * wgt;
+        den += p[DH + 1] * wgt;
+    }
+    a.out[((int64_t)b * a.L) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(num / den);
+}
+
 template <int DH>
 void run_attn(const AttnArgs& a, hipStream_t st) {
     auto kern = k_attn_bf16<DH>;
@@ -290,18 +332,33 @@ void run_attn(const AttnArgs& a, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B), dim3(NTH), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B * a.nsplit), dim3(NTH), lds, st, a);
+    if (a.nsplit > 1) hipLaunchKernelGGL(k_attn_combine<DH>, dim3(a.B * a.nh), dim3(DH), 0, st, a);
 }
 
 }  // namespace
 
-void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B, int L,
-                           int P, int n_heads, int head_dim, int max_seq, int max_batch, int layer,
+size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim) {
+    return (size_t)MAX_SPLIT * max_batch * n_heads * (head_dim + 2) * sizeof(float);
+}
+
+void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
+                           int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch, int layer,
                            hipStream_t st) {
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = L; a.P = P; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
+    // one query per sequence: too few (sequence, head) pairs to fill the chip, so the keys are split as well
+    a.nsplit = 1;
+    a.part = scratch;
+    if (L == 1 && scratch) {
+        const int tiles = (P + L - 1) / BKV + 1;
+        int ns = 1024 / (B * n_heads);
+        ns = ns > MAX_SPLIT ? MAX_SPLIT : ns;
+        ns = ns > tiles ? tiles : ns;
+        a.nsplit = ns < 1 ? 1 : ns;
+    }
     if (head_dim == 128) run_attn<128>(a, st);
     else run_attn<64>(a, st);
 }

@@ -31,6 +31,7 @@ struct mulo_ctx {
     int32_t* inputs;     // [maxM]
     int32_t* tokens_hi;  // [maxM]
     int32_t* q_row;      // [maxL]
+    float* attn_part;    // partial results of the key-split single-token attention
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
@@ -45,7 +46,7 @@ namespace {
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t off[13];
+    size_t off[14];
     size_t total;
 };
 
@@ -53,11 +54,12 @@ Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
     const size_t e = c.dtype == MULO_BF16 ? 2 : 4;
     const size_t tmpw = c.dtype == MULO_F32 ? (3 * d > 2 * f ? 3 * d : 2 * f) : 0;
-    const size_t sizes[13] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
-                              M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4};
+    const size_t sizes[14] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
+                              M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
+                              c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0};
     Layout l{};
     size_t o = 0;
-    for (int i = 0; i < 13; ++i) {
+    for (int i = 0; i < 14; ++i) {
         l.off[i] = o;
         o += align_up(sizes[i]);
     }
@@ -117,7 +119,7 @@ void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
         if (dt == MULO_BF16) {
             { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
             { PROF(MULO_PROF_ATTENTION);
-              launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, B, L, P, m.n_heads, m.head_dim, m.max_seq,
+              launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim, m.max_seq,
                                     m.max_batch, l, st); }
             { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }
             { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
@@ -279,6 +281,7 @@ mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* 
     c->inputs = (int32_t*)(b + l.off[10]);
     c->tokens_hi = (int32_t*)(b + l.off[11]);
     c->q_row = (int32_t*)(b + l.off[12]);
+    c->attn_part = (float*)(b + l.off[13]);
     *out = c;
     return MULO_OK;
 }

@@ -70,8 +70,9 @@ void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, voi
                              int d, hipStream_t st);
 void launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, int M, int V, int d,
                              hipStream_t st);
-void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
-                           int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,
+size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim);   // partial results of the key split
+void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
+                           int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,
                            int layer, hipStream_t st);
 
 // float32 path (small configurations): plain tiled GEMM + separate elementwise kernels

@@ -246,3 +246,24 @@ def test_forward_7b_hires_full_launch_sampled_sequence():
     say("  batch element 3 alone vs in the batch: max diff %.3g" % np.abs(z3 - zg[3:4]).max())
     assert np.abs(z3 - zg[3:4]).max() <= 1e-3
     del ctx, ctx1
+
+
+@pytest.mark.parametrize("dh,nh", [(64, 4), (128, 2)])
+def test_forward_single_token_steps_with_split_keys(dh, nh):
+    """Decode shape: one token per sequence against a cache of several key tiles, so that the keys are dealt
+    to several workgroups per head and combined (and the projections run in the weight-streaming kernel).
+    Cache lengths 199 .. 202 straddle a tile boundary (64-key tiles, the last one partly filled)."""
+    m = dict(n_layers=2, d_model=dh * nh, n_heads=nh, head_dim=dh, d_ffn=512, vocab=1024, dtype="bf16", rms_eps=1e-5)
+    B, Pn = 3, 199
+    w = G.make_weights(m, seed=5)
+    ctx, cos, sin = make_ctx(m, w, B, 208, 200)
+    kv = mulo.alloc_kv(ctx, DEV)
+    dr, du = pair(m, w, cos, sin, B, 208)
+    pre = G.uniform_tokens((B, Pn), m["vocab"], 5, tag=0)
+    gpu_forward(ctx, kv, pre, 0)
+    dr.forward(pre, 0)
+    du.forward(pre, 0)
+    for step in range(4):
+        t = G.uniform_tokens((B, 1), m["vocab"], 5, tag=10 + step)
+        check_bf16_logits("single token, %d cached rows, dh %d" % (Pn + step, dh), gpu_forward(ctx, kv, t, Pn + step),
+                          dr.forward(t, Pn + step).numpy(), du.forward(t, Pn + step).numpy(), strict=True)
