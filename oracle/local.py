@@ -36,3 +36,46 @@ def local_mask(accept, W, n0, radius, expand=1):
         inside = (np.abs(iu - it) <= rho) & (np.abs(ju - jt) <= rho) & (u >= t0)
         mask[inside] = 1
     return mask, t0
+
+
+def rejection_islands(mask, W, n0):
+    """Rejection islands (Sec. 3.4, Eq. 8): the 8-connected components of R_X on the 2-D token grid.
+
+    mask: bool/uint8 [L] for block positions n0 .. n0+L-1 of a grid with W columns.  Two marked positions
+    are neighbours when their rows and their columns each differ by at most one (columns do not wrap).
+    Returns (island int32 [L], rank int32 [L], n_islands, largest):
+      island[t] = 0 for an unmarked position, else 1 + the smallest block position of its island (a label
+                  that does not depend on the order in which the components are found);
+      rank[t]   = number of positions of the same island before t in raster order (-1 if unmarked): islands
+                  are re-sampled concurrently, the positions inside one in this order, so pass r handles
+                  every position of rank r and `largest` passes finish the block.
+    Plain flood fill, one island at a time."""
+    mask = np.asarray(mask).astype(bool)
+    L = mask.shape[0]
+    island = np.zeros(L, dtype=np.int32)
+    rank = np.full(L, -1, dtype=np.int32)
+    n_islands, largest = 0, 0
+    for start in range(L):
+        if not mask[start] or island[start]:
+            continue
+        n_islands += 1
+        members, stack = [], [start]
+        island[start] = start + 1
+        while stack:
+            t = stack.pop()
+            members.append(t)
+            g = n0 + t
+            i, j = g // W, g % W
+            for di in (-1, 0, 1):
+                for dj in (-1, 0, 1):
+                    jj = j + dj
+                    if (di == 0 and dj == 0) or jj < 0 or jj >= W:
+                        continue
+                    u = (i + di) * W + jj - n0
+                    if 0 <= u < L and mask[u] and not island[u]:
+                        island[u] = start + 1
+                        stack.append(u)
+        for r, t in enumerate(sorted(members)):
+            rank[t] = r
+        largest = max(largest, len(members))
+    return island, rank, n_islands, largest

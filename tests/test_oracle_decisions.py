@@ -542,3 +542,47 @@ def test_guidance_special_scales_closed_form_and_effect_on_decisions():
                   accept_mode=1, tau=0.5, mode=2, logits_uncond=np.zeros((1, 1, 2), np.float32), cfg_scale=2.0)
     assert np.allclose(h["p"][0, 0], [0.1, 0.9], atol=1e-6) and h["accept"][0, 0] == 1
     assert not np.array_equal(g["accept"], base_c["accept"]) or not np.array_equal(g["tokens_out"], base_c["tokens_out"])
+
+
+# ------------------------------------------------------------------ rejection islands (Eq. 8)
+def test_rejection_islands_match_library_labelling_and_partition_the_marked_set():
+    import scipy.ndimage
+    rng = np.random.default_rng(3)
+    eight = np.ones((3, 3), int)
+    for H, W, row0, rows, dens in [(8, 8, 0, 8, 0.3), (16, 16, 4, 8, 0.2), (12, 7, 3, 5, 0.5), (64, 64, 48, 16, 0.12), (5, 9, 0, 5, 0.9)]:
+        L, n0 = rows * W, row0 * W
+        mask = rng.random(L) < dens
+        island, rank, n, largest = LOC.rejection_islands(mask, W, n0)
+        lab, n_ref = scipy.ndimage.label(mask.reshape(rows, W), structure=eight)
+        lab = lab.reshape(-1)
+        assert n == n_ref
+        assert ((island > 0) == mask).all() and ((rank >= 0) == mask).all()
+        # same partition: a bijection between the two labellings on the marked set
+        pairs = set(zip(island[mask].tolist(), lab[mask].tolist()))
+        assert len(pairs) == n and len({a for a, _ in pairs}) == n and len({b for _, b in pairs}) == n
+        # canonical label = 1 + first member; ranks count the members before a position
+        for lbl in np.unique(island[mask]):
+            mem = np.flatnonzero(island == lbl)
+            assert lbl == mem[0] + 1 and np.array_equal(rank[mem], np.arange(mem.size))
+        assert largest == (np.bincount(lab[mask]).max() if mask.any() else 0)
+
+
+def test_rejection_islands_hand_examples():
+    # diagonal neighbours join (8-connectivity; a 4-connected labelling would report three islands)
+    m = np.array([1, 0, 0,
+                  0, 1, 0,
+                  0, 0, 1], bool)
+    island, rank, n, largest = LOC.rejection_islands(m, 3, 0)
+    assert n == 1 and largest == 3 and island.tolist() == [1, 0, 0, 0, 1, 0, 0, 0, 1] and rank[[0, 4, 8]].tolist() == [0, 1, 2]
+    # the last column of a row and the first column of the next are NOT neighbours (no wrap) ...
+    m = np.array([0, 0, 1,
+                  1, 0, 0], bool)
+    assert LOC.rejection_islands(m, 3, 0)[2] == 2
+    # ... and a block that starts in the middle of the grid uses the true coordinates
+    assert LOC.rejection_islands(m, 3, 9)[2] == 2
+    m = np.array([0, 1, 1, 0,
+                  0, 0, 0, 0,
+                  1, 0, 0, 1], bool)
+    island, rank, n, largest = LOC.rejection_islands(m, 4, 8)
+    assert n == 3 and largest == 2 and island.tolist() == [0, 2, 2, 0, 0, 0, 0, 0, 9, 0, 0, 12]
+    assert LOC.rejection_islands(np.zeros(6, bool), 3, 0)[2:] == (0, 0)
