@@ -233,6 +233,17 @@ MULO_API mulo_status mulo_resample_sequential(mulo_ctx *ctx, mulo_kv *kv, int32_
                                      const int32_t *prev_tokens, const uint8_t *mask, int32_t *tokens,
                                      float *logits);
 
+/* Rejection islands (Sec. 3.4, Eq. 8): the 8-connected components of the marked set R_X on the 2-D token grid
+ * (rows and columns each differ by at most one; columns do not wrap; only positions of the block exist).
+ *   mask    device uint8 [B, L]  R_X of the block that starts at grid position n0 (whole rows of W columns)
+ *   island  device int32 [B, L]  (out) 0 where unmarked, else 1 + the smallest block position of the island
+ *   rank    device int32 [B, L]  (out) -1 where unmarked, else the number of positions of the same island that
+ *           precede it in raster order: islands are re-sampled concurrently, pass r takes every rank-r position
+ *   counts  device int32 [B, 2]  (out) number of islands, size of the largest (= number of passes)
+ * Errors: L not a multiple of W, n0 not on a row start, L > 16384 -> MULO_ERR_SHAPE / MULO_ERR_UNSUPPORTED. */
+MULO_API mulo_status mulo_rejection_islands(mulo_ctx *ctx, int32_t B, int32_t W, int32_t n0, int32_t L,
+                                   const uint8_t *mask, int32_t *island, int32_t *rank, int32_t *counts);
+
 /* Optional per-kernel timing (measurement aid, not part of the method).  While
  * enabled, every kernel launch of the entry points above is bracketed by a pair
  * of HIP events on the context's stream.  mulo_profile_read synchronises the

@@ -441,6 +441,68 @@ __global__ __launch_bounds__(TPB) void k_seq_draw(const float* __restrict__ logi
     cdf_draw(z, reinterpret_cast<const float4*>(z.zc), m, inv, true, word, V, *out, out, chunk, &s_retry);
 }
 
+// ---- rejection islands (Eq. 8): 8-connected components of the marked set, one workgroup per sequence ----
+// Labels live in LDS (one int per block position: 0 = unmarked, else 1 + a member's position).  Every round
+// a marked position takes the smallest label among itself and its 8 grid neighbours and then jumps to the
+// label of the position that label names (pointer jumping), until a round changes nothing: each island ends
+// with 1 + its smallest position.  The rank of a position is the number of members of its island before it.
+__global__ __launch_bounds__(TPB) void k_islands(const uint8_t* __restrict__ mask, int32_t* __restrict__ island,
+                                                 int32_t* __restrict__ rank, int32_t* __restrict__ counts, int W,
+                                                 int n0, int L) {
+    extern __shared__ int lab[];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const uint8_t* mk = mask + (int64_t)b * L;
+    for (int t = tid; t < L; t += TPB) lab[t] = mk[t] ? t + 1 : 0;
+    __syncthreads();
+    while (true) {
+        int changed = 0;
+        for (int t = tid; t < L; t += TPB) {
+            int cur = lab[t];
+            if (!cur) continue;
+            const int g = n0 + t, i = g / W, j = g % W;
+            int best = cur;
+#pragma unroll
+            for (int di = -1; di <= 1; ++di)
+#pragma unroll
+                for (int dj = -1; dj <= 1; ++dj) {
+                    const int jj = j + dj, u = (i + di) * W + jj - n0;
+                    if (jj >= 0 && jj < W && u >= 0 && u < L) {
+                        const int v = lab[u];
+                        if (v && v < best) best = v;
+                    }
+                }
+            const int hop = lab[best - 1];       // the named position is marked, so its label is > 0
+            if (hop < best) best = hop;
+            if (best < cur) { atomicMin(&lab[t], best); changed = 1; }
+        }
+        if (!__syncthreads_or(changed)) break;
+    }
+    int n_isl = 0, largest = 0;
+    for (int t = tid; t < L; t += TPB) {
+        const int l = lab[t];
+        int r = -1;
+        if (l) {
+            r = 0;
+            for (int u = l - 1; u < t; ++u) r += lab[u] == l;
+            if (l == t + 1) {                     // the island's first member counts the island and measures it
+                ++n_isl;
+                int sz = 0;
+                for (int u = t; u < L; ++u) sz += lab[u] == l;
+                largest = sz > largest ? sz : largest;
+            }
+        }
+        island[(int64_t)b * L + t] = l;
+        rank[(int64_t)b * L + t] = r;
+    }
+    __shared__ int red_n, red_m;
+    if (tid == 0) { red_n = 0; red_m = 0; }
+    __syncthreads();
+    if (n_isl) atomicAdd(&red_n, n_isl);
+    if (largest) atomicMax(&red_m, largest);
+    __syncthreads();
+    if (tid == 0) { counts[b * 2] = red_n; counts[b * 2 + 1] = red_m; }
+}
+
 template <int NV4>
 void softmax_rows_inst(const float* in, float* out, int64_t rows, int V, hipStream_t st) {
     hipLaunchKernelGGL(k_softmax_rows<NV4>, dim3((unsigned)rows), dim3(TPB), 0, st, in, out, V);
@@ -487,6 +549,11 @@ void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t*
     const int64_t n = (int64_t)B * L;
     hipLaunchKernelGGL(k_shift_inputs, dim3((unsigned)((n + TPB - 1) / TPB)), dim3(TPB), 0, st, prev,
                        tokens_hi, inputs, B, L);
+}
+
+void launch_islands(const uint8_t* mask, int32_t* island, int32_t* rank, int32_t* counts, int B, int W, int n0, int L,
+                    hipStream_t st) {
+    hipLaunchKernelGGL(k_islands, dim3(B), dim3(TPB), (size_t)L * sizeof(int), st, mask, island, rank, counts, W, n0, L);
 }
 
 void launch_seq_input(const int32_t* prev, const int32_t* tokens, int32_t* inp, int B, int L, int u, hipStream_t st) {

@@ -421,4 +421,15 @@ mulo_status mulo_resample_sequential(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int3
     return check_launch();
 }
 
+mulo_status mulo_rejection_islands(mulo_ctx* ctx, int32_t B, int32_t W, int32_t n0, int32_t L, const uint8_t* mask,
+                                   int32_t* island, int32_t* rank, int32_t* counts) {
+    if (!ctx || !mask || !island || !rank || !counts) return MULO_ERR_NULL;
+    if (B < 1 || W < 1 || L < 1 || n0 < 0) return MULO_ERR_RANGE;
+    if (L % W != 0 || n0 % W != 0) return MULO_ERR_SHAPE;
+    if (L > 16384) return MULO_ERR_UNSUPPORTED;      // labels of a block live in LDS
+    mulo_ctx* c = ctx;
+    { PROF(MULO_PROF_OTHER); launch_islands(mask, island, rank, counts, B, W, n0, L, ctx->st); }
+    return check_launch();
+}
+
 }  // extern "C"

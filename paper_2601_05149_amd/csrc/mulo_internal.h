@@ -40,6 +40,8 @@ void launch_upsample_tokens(const int32_t* draft_tokens, int32_t* tokens_hi, int
                             int h, int w, int r, hipStream_t st);
 void launch_gather_rows(const float* q_lo, const int32_t* q_row, float* q_hi, int B, int n_lo,
                         int n_hi, int V, hipStream_t st);
+void launch_islands(const uint8_t* mask, int32_t* island, int32_t* rank, int32_t* counts, int B, int W, int n0, int L,
+                    hipStream_t st);
 void launch_seq_input(const int32_t* prev, const int32_t* tokens, int32_t* inp, int B, int L, int u, hipStream_t st);
 void launch_seq_draw(const float* logits, const uint8_t* mask, int32_t* tokens, int B, int L, int V, int u,
                      uint64_t seed, uint64_t rng_counter, hipStream_t st);

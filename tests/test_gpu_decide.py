@@ -332,3 +332,58 @@ def test_guided_decide_parity(B, V, scale, amode):
         mulo.mulo_accept_local_resample(ctx, 3, params, dev(z2, torch.float32), dev(q, torch.float32), None, L * V,
                                         dev(toks, torch.int32), out["tokens_out"], out["accept"], out["mask"], out["t0"],
                                         out["stats"], None)
+
+
+# --------------------------------------------------------------- rejection islands (Eq. 8)
+def _islands_gpu(ctx, mask, W, n0):
+    B, L = mask.shape
+    isl = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    rk = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(B, 2, dtype=torch.int32, device=DEV)
+    mulo.mulo_rejection_islands(ctx, B, W, n0, L, dev(mask.astype(np.uint8), torch.uint8), isl, rk, cnt)
+    torch.cuda.synchronize()
+    return isl.cpu().numpy(), rk.cpu().numpy(), cnt.cpu().numpy()
+
+
+def test_rejection_islands_parity():
+    from oracle import local as LOC
+    ctx = decide_ctx(1024, 4, 1024)
+    rng = np.random.default_rng(12)
+    cases = [(8, 0, 8, 0.3), (16, 4, 8, 0.2), (7, 3, 5, 0.5), (64, 48, 16, 0.12), (64, 0, 64, 0.25), (9, 0, 5, 0.95), (48, 36, 12, 0.0)]
+    for W, row0, rows, dens in cases:
+        L, n0 = rows * W, row0 * W
+        mask = rng.random((3, L)) < dens
+        # a serpentine path: the slowest case for label propagation (one island that winds through every other row)
+        snake = np.zeros((rows, W), bool)
+        snake[::2] = True
+        for r in range(1, rows, 2):
+            snake[r, W - 1 if (r // 2) % 2 == 0 else 0] = True
+        mask[2] = snake.reshape(-1)
+        isl, rk, cnt = _islands_gpu(ctx, mask, W, n0)
+        for b in range(3):
+            ri, rr, n, largest = LOC.rejection_islands(mask[b], W, n0)
+            assert np.array_equal(isl[b], ri) and np.array_equal(rk[b], rr), (W, row0, rows, dens, b)
+            assert cnt[b].tolist() == [n, largest]
+        say("  islands W=%d rows=%d density %.2f: %s islands, largest %s" % (W, rows, dens, cnt[:, 0].tolist(), cnt[:, 1].tolist()))
+    with pytest.raises(mulo.MuloError):
+        _islands_gpu(ctx, np.zeros((1, 30), bool), 8, 0)       # not whole rows
+    with pytest.raises(mulo.MuloError):
+        _islands_gpu(ctx, np.zeros((1, 32), bool), 8, 4)       # block does not start on a row
+
+
+def test_rejection_islands_of_a_decided_block():
+    """Islands of the mask that the decision stage produced (radius-1 neighbourhoods of scattered rejections)."""
+    from oracle import local as LOC
+    B, H, W, L, V = 2, 32, 32, 1024, 1024
+    ctx = decide_ctx(V, 4, 1024)
+    zp, q, toks = clean_inputs(B, L, V, 0.35, seed=4)
+    # the paper's threshold rule with a low threshold: a few scattered rejections
+    got = run_decide(ctx, zp, None, toks, H=H, W=W, n0=0, L=L, radius=1, expand=1, seed=1, rng_counter=2,
+                     resample_mode=2, accept_mode=mulo.MULO_ACCEPT_TAU, tau=1e-4)
+    isl, rk, cnt = _islands_gpu(ctx, got["mask"].astype(bool), W, 0)
+    for b in range(B):
+        ri, rr, n, largest = LOC.rejection_islands(got["mask"][b], W, 0)
+        assert np.array_equal(isl[b], ri) and np.array_equal(rk[b], rr) and cnt[b].tolist() == [n, largest]
+    say("  decided block: marked %.3f, islands %s, passes %s (sequential would need %s)" % (
+        got["mask"].mean(), cnt[:, 0].tolist(), cnt[:, 1].tolist(), got["mask"].sum(1).tolist()))
+    assert (cnt[:, 0] > 1).all() and (cnt[:, 1] < got["mask"].sum(1)).all()
