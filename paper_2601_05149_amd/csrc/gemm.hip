@@ -61,14 +61,14 @@ __device__ __forceinline__ void static_for(F&& f) {
 // g * sigmoid(g) with the hardware reciprocal (1 ulp; the product is rounded to bf16 right after)
 __device__ __forceinline__ float silu(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
-// Source row of weight-tile row nl (fixed over the K loop) for each fused problem.
+// Source of weight-tile row nl (fixed over the K loop) for each fused problem: row index, and which of the
+// two weight matrices (0: W0, 1: W1) it belongs to.
 template <int EPI, int BN, int TN>
-__device__ __forceinline__ const bf16* b_row(const GemmArgs& g, int n0, int tile_n, int nl) {
-    const bf16* base;
+__device__ __forceinline__ int b_row_src(const GemmArgs& g, int n0, int tile_n, int nl, int& which) {
     int r;
     if constexpr (EPI == EPI_QK) {
         const int seg = n0 / g.d;
-        base = seg == 0 ? g.W0 : g.W1;
+        which = seg;
         r = n0 - seg * g.d + nl;
     } else if constexpr (EPI == EPI_SWIGLU) {
         // tile covers feed-forward columns [f0, f0 + BN/2); the wavefront owning tile columns
@@ -77,13 +77,35 @@ __device__ __forceinline__ const bf16* b_row(const GemmArgs& g, int n0, int tile
         const int w_ = nl / TN, within = nl % TN;
         r = f0 + w_ * (TN / 2) + (within % (TN / 2));
         r = r < f ? r : f - 1;
-        base = within >= TN / 2 ? g.W1 : g.W0;
+        which = within >= TN / 2 ? 1 : 0;
     } else {
-        base = g.W0;
+        which = 0;
         r = n0 + nl;
         r = r < g.N ? r : g.N - 1;
     }
-    return base + (int64_t)r * g.K;
+    return r;
+}
+template <int EPI, int BN, int TN>
+__device__ __forceinline__ const bf16* b_row(const GemmArgs& g, int n0, int tile_n, int nl) {
+    int which;
+    const int r = b_row_src<EPI, BN, TN>(g, n0, tile_n, nl, which);
+    return (which ? g.W1 : g.W0) + (int64_t)r * g.K;
+}
+
+// Whole-tile launches address their operands through buffer descriptors: the descriptor (matrix base and size)
+// and a byte offset of the tile row and K-step live in scalar registers, a lane adds one fixed 32-bit offset
+// (its row and 16-byte chunk inside a pass).  No 64-bit lane addresses to keep or to advance.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, int64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)(bytes < 0x7fffffff ? bytes : 0x7fffffff), 0x00020000);
+}
+__device__ __forceinline__ u32x4 bload(rsrc_t r, uint32_t lane_off, uint32_t base_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)base_off, 0);
+}
+// rows of the weight matrices of each fused problem
+template <int EPI>
+__device__ __forceinline__ int64_t weight_rows(const GemmArgs& g) {
+    return EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N;
 }
 
 // Which tile row feeds MFMA row rho: bits 2 and 3 exchanged.  With it, accumulator r of a lane
@@ -241,14 +263,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     const int kc8 = (tid % CPR) * 8, trow = tid / CPR;
     // Operand addresses.  General case: one pointer per staged chunk.  FULL (M and N multiples of the
     // tile, the launcher checks): the rows a lane fetches are a fixed stride apart, so a lane keeps
-    // ONE 32-bit offset (its row and chunk inside a 64-row pass) and the pass bases are wavefront-
-    // uniform scalars: global_load with a scalar base, 15 vector registers fewer.
+    // ONE 32-bit offset (its row and chunk inside a pass) and everything else is scalar: buffer loads
+    // through a descriptor of the whole matrix, with the pass's row and the K-step as scalar offset.
+    // No 64-bit lane addresses to keep or to advance (about 25 vector registers fewer).
     constexpr int RP = NT / CPR;   // tile rows per pass
     const bf16* pa[FULL ? 1 : LA];
     const bf16* pb[FULL ? 1 : LB];
-    const char* sa[FULL ? LA : 1];
-    const char* sb[FULL ? LB : 1];
+    uint32_t sa[FULL ? LA : 1];   // byte offset of pass i's first row in its matrix
+    uint32_t sb[FULL ? LB : 1];
     const uint32_t voff = (uint32_t)(trow * g.K + kc8) * 2u;
+    const rsrc_t rA = make_rsrc(g.A, (int64_t)g.M * g.K * 2);
+    rsrc_t rW[2] = {make_rsrc(g.W0, weight_rows<EPI>(g) * g.K * 2),
+                    make_rsrc(EPI == EPI_QK || EPI == EPI_SWIGLU ? g.W1 : g.W0, weight_rows<EPI>(g) * g.K * 2)};
+    // which descriptor pass i of the weight tile reads: gate | up alternate inside a tile (compile-time), q | k is per tile
+    auto wsel = [&](int i) -> rsrc_t { return rW[EPI == EPI_SWIGLU ? ((i * RP) % TN >= TN / 2 ? 1 : 0) : 0]; };
     auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
         const int t = chunk_base + local, grp = t / (tiles_m * GW), rem = t - grp * tiles_m * GW;
         const int gw = g.tiles_n - grp * GW < GW ? g.tiles_n - grp * GW : GW;
@@ -257,9 +285,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
         n0 = tile_n * BN;
         if constexpr (FULL) {
 #pragma unroll
-            for (int i = 0; i < LA; ++i) sa[i] = reinterpret_cast<const char*>(g.A + (int64_t)(m0 + i * RP) * g.K);
+            for (int i = 0; i < LA; ++i) sa[i] = (uint32_t)((m0 + i * RP) * g.K) * 2u;
 #pragma unroll
-            for (int i = 0; i < LB; ++i) sb[i] = reinterpret_cast<const char*>(b_row<EPI, BN, TN>(g, n0, tile_n, i * RP));
+            for (int i = 0; i < LB; ++i) {
+                int which;
+                sb[i] = (uint32_t)(b_row_src<EPI, BN, TN>(g, n0, tile_n, i * RP, which) * g.K) * 2u;
+                if constexpr (EPI == EPI_QK) { if (i == 0) rW[0] = make_rsrc(which ? g.W1 : g.W0, weight_rows<EPI>(g) * g.K * 2); }
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < LA; ++i) {
@@ -277,9 +309,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     auto gload = [&](int kt) {
         if constexpr (FULL) {
 #pragma unroll
-            for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(sa[i] + kt * (BK * 2) + voff);
+            for (int i = 0; i < LA; ++i) ra[i] = bload(rA, voff, sa[i] + kt * (BK * 2));
 #pragma unroll
-            for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const u32x4*>(sb[i] + kt * (BK * 2) + voff);
+            for (int i = 0; i < LB; ++i) rb[i] = bload(wsel(i), voff, sb[i] + kt * (BK * 2));
         } else {
 #pragma unroll
             for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + kt * BK);
@@ -298,30 +330,60 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
         for (int i = 0; i < LB; ++i)
             *reinterpret_cast<u32x4*>(b + (trow + i * (NT / CPR)) * LDS_STRIDE + kc8) = rb[i];
     };
-    bf16x8 af[2][MB], bfr[2][NB];   // fragments of one k-step, double-buffered in registers
+    // Fragments of one k-slice, double-buffered in registers.  Inside a 64-deep K-step the k index is dealt so that
+    // lane half lh owns k in [32 lh, 32 lh + 32) and MFMA slice kk takes its kk-th 8 (both operands alike, so the
+    // products are unchanged): the same deal, hence the same summation order, as in the kernels that fetch an
+    // operand straight from memory, where it makes a lane's bytes contiguous.
+    bf16x8 af[2][MB], bfr[2][NB];
     auto lfrag = [&](const bf16* a, const bf16* b, int kk, int slot) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
-            af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + kk * 16);
+            af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + kk * 8);
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-            bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 16);
+            bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 8);
     };
 
     // Pipeline over the flattened sequence of K-steps of all this workgroup's tiles.  While step s is
-    // multiplied out of LDS buffer s & 1, step s+1 is in flight into the staging registers; at the end
-    // of the iteration it is written to the other buffer and step s+2 is requested AT ONCE, before the
-    // barrier: the requests then have the barrier wait and the whole next multiply phase to complete
-    // (their latency, about 1500 cycles, is most of a multiply phase), and the burst that fills the
-    // memory pipeline's queue stalls wavefronts that are about to wait at the barrier anyway.  Near the
-    // end of a tile the requests run ahead into the next tile, whose first step is staged while this
-    // tile's epilogue runs.  The launcher guarantees nk >= 2.
+    // multiplied out of LDS buffer s & 1, step s+1 is in flight into the staging registers; spread over
+    // the iteration's MFMAs, every staging register is written to the other buffer and requested again
+    // at once for step s+2, so each request has a whole iteration to land and the memory pipeline sees
+    // one request per few MFMAs instead of a burst.  Near the end of a tile the requests run ahead into
+    // the next tile, whose first step is staged while this tile's epilogue runs.  The launcher
+    // guarantees nk >= 2.
     if (tile >= chunk_len) return;   // uniform over the workgroup, before any barrier
     setup(tile);
     gload(0);
     sstore(0);
     gload(1);
     __syncthreads();
+    constexpr int KS = BK / 16;                      // k-slices (one MFMA deep) per K-step
+    constexpr int NMS = MB * NB, NF = MB + NB;       // MFMAs and fragment reads per k-slice
+    constexpr int NL = LA + LB;                      // staging registers per lane
+    static_assert(KS == 4, "the rotated loop is written for 4 k-slices per K-step");
+    auto mm = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[slot][i], bfr[slot][j], acc[i][j]);
+    };
+    // One K-step, rotated by one k-slice: the step's first fragments are requested right after the barrier and
+    // the MFMAs of the PREVIOUS step's last slice (fragments already in registers, slot 1) run while they are on
+    // their way, so no wavefront waits for LDS with an empty MFMA queue.  Slice kk lives in slot kk & 1; on return
+    // slot 1 holds the step's last slice, not yet multiplied.
+    auto step_rot = [&](int step) {
+        const bf16* a = sA + (step & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * (BK / 2);
+        const bf16* b = sB + (step & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * (BK / 2);
+        lfrag(a, b, 0, 0);
+        mm(1);
+        lfrag(a, b, 1, 1);
+        mm(0);
+        lfrag(a, b, 2, 0);
+        mm(1);
+        lfrag(a, b, 3, 1);
+        mm(0);
+    };
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     int gs = 0;   // steps done so far: buffer parity
     while (true) {
 #pragma unroll
@@ -330,44 +392,67 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
             for (int j = 0; j < NB; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        // nothing is pending at the start of a tile: slot 1 holds zeros, its MFMAs add nothing
+#pragma unroll
+        for (int i = 0; i < MB; ++i) af[1][i] = zero8;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) bfr[1][j] = zero8;
         int e_m0 = m0, e_n0 = n0, e_tile_n = tile_n;
         bool more = true;
-        auto multiply = [&](int step) {   // K-step `step` out of LDS buffer step & 1
-            const bf16* a = sA + (step & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 8;
-            const bf16* b = sB + (step & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 8;
-            lfrag(a, b, 0, 0);
-#pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                if (kk + 1 < BK / 16) lfrag(a, b, kk + 1, (kk + 1) & 1);
-#pragma unroll
-                for (int i = 0; i < MB; ++i)
-#pragma unroll
-                    for (int j = 0; j < NB; ++j) acc[i][j] = mma<SWAP>(af[kk & 1][i], bfr[kk & 1][j], acc[i][j]);
-            }
-        };
         int kt = 0;
-        // steady state: one scheduling region per K-step.  The first half of the MFMAs runs with the
-        // fragment reads; in the second half every staging register is written to LDS as soon as its
-        // load (requested one iteration ago) is there and is at once requested again for step kt + 2.
+        // steady state: one scheduling region per K-step.  Fragment reads of slice kk + 1 go in front of the MFMAs
+        // of slice kk; over the MFMAs of the step's slices 1 and 2 every staging register is written to LDS as soon
+        // as its load (requested one iteration ago) is there and is at once requested again for step kt + 2.
         for (; kt < nk - 2; ++kt, ++gs) {
-            multiply(gs);
-            sstore((gs + 1) & 1);
-            gload(kt + 2);
-            {
-                constexpr int NL = LA + LB, NM = MB * NB * (BK / 16);
-                constexpr int TAIL = NM >= 4 * NL ? 2 : 1, HEAD = NM - TAIL * NL;
-                if (HEAD > 0) __builtin_amdgcn_sched_group_barrier(0x008, HEAD > 0 ? HEAD : 1, 0);
-#pragma unroll
-                for (int i = 0; i < NL; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);      // LDS write of staging register i
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);      // its next global load
-                    __builtin_amdgcn_sched_group_barrier(0x008, TAIL, 0);
+            const bf16* a = sA + (gs & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * (BK / 2);
+            const bf16* b = sB + (gs & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * (BK / 2);
+            bf16* na = sA + ((gs + 1) & 1) * BM * LDS_STRIDE + trow * LDS_STRIDE + kc8;
+            bf16* nb = sB + ((gs + 1) & 1) * BN * LDS_STRIDE + trow * LDS_STRIDE + kc8;
+            auto stage = [&](auto ic) {   // staging register i: to LDS (step kt + 1), then requested again (step kt + 2)
+                constexpr int i = decltype(ic)::value;
+                if constexpr (i < LA) {
+                    *reinterpret_cast<u32x4*>(na + i * RP * LDS_STRIDE) = ra[i];
+                    if constexpr (FULL) ra[i] = bload(rA, voff, sa[i] + (kt + 2) * (BK * 2));
+                    else ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + (kt + 2) * BK);
+                } else {
+                    constexpr int j = i - LA;
+                    *reinterpret_cast<u32x4*>(nb + j * RP * LDS_STRIDE) = rb[j];
+                    if constexpr (FULL) rb[j] = bload(wsel(j), voff, sb[j] + (kt + 2) * (BK * 2));
+                    else rb[j] = *reinterpret_cast<const u32x4*>(pb[j] + (kt + 2) * BK);
                 }
-            }
+            };
+            // The NL write + load pairs are dealt evenly over the first SPAN MFMAs of the iteration; the rest run
+            // bare, so the last LDS writes have landed when the wavefront reaches the barrier.
+            constexpr int SPAN = 4 * NMS - NMS / 2;
+            auto before = [](int m) constexpr { return m >= SPAN ? NL : m * NL / SPAN; };   // pairs in front of MFMA m
+            auto phase = [&](auto phc, int kk_next, int slot_next, int slot) {
+                constexpr int ph = decltype(phc)::value;
+                if (kk_next >= 0) lfrag(a, b, kk_next, slot_next);
+                static_for<before((ph + 1) * NMS) - before(ph * NMS)>(
+                    [&](auto ic) { stage(std::integral_constant<int, before(ph * NMS) + decltype(ic)::value>{}); });
+                mm(slot);
+            };
+            phase(std::integral_constant<int, 0>{}, 0, 0, 1);   // previous step's last slice
+            phase(std::integral_constant<int, 1>{}, 1, 1, 0);
+            phase(std::integral_constant<int, 2>{}, 2, 0, 1);
+            phase(std::integral_constant<int, 3>{}, 3, 1, 0);
+            static_for<4>([&](auto phc) {
+                constexpr int ph = decltype(phc)::value;
+                __builtin_amdgcn_sched_group_barrier(0x100, NF, 0);
+                static_for<NMS>([&](auto mc) {
+                    constexpr int m = ph * NMS + decltype(mc)::value;
+                    static_for<before(m + 1) - before(m)>([&](auto) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    });
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                });
+            });
+            __builtin_amdgcn_sched_barrier(0);   // the bare MFMAs stay in front of the barrier
             __syncthreads();
         }
         for (; kt < nk; ++kt, ++gs) {   // last two steps of the tile: the requests move on to the next tile
-            multiply(gs);
+            step_rot(gs);
             if (kt == nk - 2) {
                 e_m0 = m0; e_n0 = n0; e_tile_n = tile_n;
                 tile += tile_stride;
@@ -378,10 +463,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
             if (more) gload(kt + 2 - nk);
             __syncthreads();
         }
+        mm(1);   // the tile's last slice
         epilogue<EPI, BN, TM, TN, MB, NB>(g, acc, e_m0, e_n0, e_tile_n, wm, wn, l32, lh);
         if (!more) break;
     }
 }
+
 
 static int cu_count() {
     static int n = 0;
@@ -410,6 +497,7 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
     g.tile_n0 = tile_n0;
     hipLaunchKernelGGL(kern, dim3(total < resident ? total : resident), dim3(WGM * WGN * 64), lds, st, g);
 }
+
 
 // ---- up to 32 tokens (single-token decoding of a few sequences): weight-streaming kernel ------------
 // The work is reading every weight once, so nothing is staged: a workgroup owns 32 output columns (for
@@ -543,7 +631,8 @@ void dispatch(const GemmArgs& g, hipStream_t st) {
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
     const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
-                      (int64_t)g.K * 256 * 2 < (1ll << 31) &&
+                      (int64_t)g.K * 256 * 2 < (1ll << 31) && (int64_t)g.M * g.K * 2 < (1ll << 31) &&
+                      (int64_t)(EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N) * g.K * 2 < (1ll << 31) &&
                      (int64_t)(g.M / 256) * (g.N / 256) * 4 >= 3 * (int64_t)cu_count();   // enough 256x256 tiles to fill the chip
     if (big) {
         // Whole rounds of 256x256 tiles, one tile per CU and round.  A last round that would leave more than
