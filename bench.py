@@ -155,11 +155,16 @@ def main():
     torch.cuda.synchronize()
     if not a.no_profile:
         mulo.mulo_profile(ctx, 1 if a.profile_all else 0x100 | PROF_CLASSES.index("gemm_gate_up"))
+    # per-step marks on the library's stream (torch's current one): recorded, not waited for, inside the timed region
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     t_start = time.perf_counter()
+    marks[0].record()
     for i in range(a.steps):
         step(a.warmup + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt_s = time.perf_counter() - t_start
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
     prof = mulo.mulo_profile_read(ctx) if not a.no_profile else {}
     mulo.mulo_profile(ctx, 0)
     ms_per_step = 1e3 * dt_s / a.steps
@@ -215,6 +220,7 @@ def main():
                                                                     c["radius"], sigma),
                       "acceptance_rate": round(acc_rate, 4), "marked_fraction": round(marked, 4)},
            "accepted_tokens_per_s": round(M * (1.0 - marked) / (ms_per_step * 1e-3), 1),
+           "ms_per_step_median": round(per_step[len(per_step) // 2], 3), "ms_per_step_min": round(per_step[0], 3),
            "step_tflops": round(fwd_flops / (ms_per_step * 1e-3) / 1e12, 1),
            "step_frac_of_bf16_peak": round(fwd_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
            "roofline": roof, "kernels": kernels}

@@ -84,8 +84,9 @@ def compare_step_with_oracle(gpu, ref, logit_tol, label):
     return dict(flips=int(diff.sum()), movable=int(movable.sum()), tok_mismatch=n_tok)
 
 
-def test_step_tiny_f32_vs_oracle_and_composition():
-    c = WC.get("cfg1")
+@pytest.mark.parametrize("name", ["cfg1", "cfg1_r4"])
+def test_step_tiny_f32_vs_oracle_and_composition(name):
+    c = WC.get(name)
     m, B, L, Pn, V = c["model"], c["B"], c["L"], c["prefix"], c["model"]["vocab"]
     w = G.make_weights(m, seed=0)
     ctx, cos, sin = make_ctx(m, w, B, c["max_seq"], L)
@@ -103,7 +104,8 @@ def test_step_tiny_f32_vs_oracle_and_composition():
     gn = to_np(g)
     err = np.abs(gn["logits"] - ref["logits"]).max()
     rep = compare_step_with_oracle(gn, ref, 1e-4, "tiny step")
-    say("  tiny step: max|logit err| %.3g acc %.3f marked %.3f %r" % (err, ref["accept"].mean(), ref["mask"].mean(), rep))
+    say("  tiny step %s (ratio %d, radius %d): max|logit err| %.3g acc %.3f marked %.3f %r"
+        % (name, c["r"], c["radius"], err, ref["accept"].mean(), ref["mask"].mean(), rep))
     assert err <= 1e-4
 
 

@@ -1,4 +1,4 @@
-"""The five synthetic workloads (shapes follow the paper's: 16x VQ grids of
+"""The synthetic workloads (shapes follow the paper's: 16x VQ grids of
 256-4096 tokens, whole-row draft blocks, a prefilled conditioning prefix, a
 LlamaGen-class decoder; supplement "Primer on Tar").  Data only: no arithmetic
 of the method lives here.
@@ -31,6 +31,11 @@ CONFIGS = {
                       sigma=1.0, seed=0),
     "cfg5_L1024": dict(model="7b", prefix=128, h=32, w=32, r=2, L=1024, B=16, radius=1, expand=1,
                        sigma=1.0, seed=0),
+    # the paper's best setting (Sec. 4, ratio 4: a 16x16 draft of the 64x64 grid; radius 3): data-only variants
+    "cfg1_r4": dict(model="tiny", prefix=32, h=4, w=4, r=4, L=256, B=2, radius=3, expand=1,
+                    sigma=None, draft_std=2.0, seed=0),
+    "cfg4_r4": dict(model="7b", prefix=128, h=16, w=16, r=4, L=1024, B=4, radius=3, expand=1,
+                    sigma=1.0, seed=0),
 }
 
 
