@@ -1,9 +1,12 @@
 // Causal attention of the drafted block over prefix + block (Alg. 1 Step 3: the
 // j-th conditional sees cache rows 0 .. P+j).
 //
-// bf16 path: flash-style, one workgroup of 4 wavefronts per (128 queries, head,
-// sequence); K and V^T tiles of 64 keys are staged through LDS (double buffered)
-// and shared by the 4 wavefronts; each wavefront owns 32 queries and computes
+// bf16 path: flash-style, one workgroup of 8 wavefronts (two per SIMD) per (256
+// queries, head, sequence); K and V^T tiles of 128 keys are staged through LDS
+// (double buffered, 139 KB) and shared by the 8 wavefronts, so a tile is fetched and
+// written to LDS once per 256 queries and the per-tile work (barrier, running
+// maximum, rescale test) is spread over 32 MFMAs per product; each wavefront owns
+// 32 queries and computes
 // S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so that a lane
 // owns ONE query: the softmax row reductions stay inside the lane (plus one
 // cross-half shuffle), and the exponentiated scores are already laid out as the
@@ -24,7 +27,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __hip_bfloat16 bf16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int BQ = 128, BKV = 64, NTH = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct AttnArgs {
@@ -39,8 +41,8 @@ struct AttnArgs {
 };
 constexpr int MAX_SPLIT = 16;
 
-template <int DH>
-__global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
+template <int DH, int BQ, int BKV, int NTH>
+__global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const AttnArgs a) {
     constexpr int KS = DH + 8;     // K tile row stride (bf16)
     constexpr int VS = BKV + 8;    // V^T tile row stride
     constexpr int NKK = DH / 16;   // k-steps of the first product
@@ -167,9 +169,9 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             gload(t_next);
             const bf16* k = sK + (t & 1) * BKV * KS;
             const bf16* v = sV + (t & 1) * DH * VS;
-            f32x16 s[2];
+            f32x16 s[BKV / 32];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < BKV / 32; ++kb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
                 const bf16* kr = k + (kb * 32 + kperm) * KS + lh * 8;
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             float mx = -__builtin_huge_valf();
             if (need_mask) {
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
                     }
             }
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -200,9 +202,9 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             float ps = 0.f;
-            bf16x8 pf[4];
+            bf16x8 pf[BKV / 16];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], a.scale_log2, -m_new));
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(NTH, 2) void k_attn_bf16(const AttnArgs a) {
             }
             // O^T += V^T P^T : k-step ks covers keys kv0 + 16 ks .. +15
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
+            for (int ks = 0; ks < BKV / 16; ++ks) {
 #pragma unroll
                 for (int i = 0; i < NDB; ++i) {
                     const bf16x8 vf = *reinterpret_cast<const bf16x8*>(v + (i * 32 + l32) * VS + ks * 16 + lh * 8);
@@ -322,9 +324,9 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
     a.out[((int64_t)b * a.L) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(num / den);
 }
 
-template <int DH>
-void run_attn(const AttnArgs& a, hipStream_t st) {
-    auto kern = k_attn_bf16<DH>;
+template <int DH, int BQ, int BKV, int NTH>
+void run_attn_cfg(const AttnArgs& a, hipStream_t st) {
+    auto kern = k_attn_bf16<DH, BQ, BKV, NTH>;
     const size_t lds = (size_t)2 * (BKV * (DH + 8) + DH * (BKV + 8)) * sizeof(bf16);
     static bool attr_set = false;
     if (!attr_set) {
@@ -334,6 +336,15 @@ void run_attn(const AttnArgs& a, hipStream_t st) {
     }
     hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B * a.nsplit), dim3(NTH), lds, st, a);
     if (a.nsplit > 1) hipLaunchKernelGGL(k_attn_combine<DH>, dim3(a.B * a.nh), dim3(DH), 0, st, a);
+}
+
+// Blocks of more than 128 queries: 256-query workgroups of 8 wavefronts over 128-key tiles (one per CU).  Shorter
+// ones (single-token decoding above all): 128-query workgroups of 4 wavefronts over 64-key tiles, two per CU.
+constexpr int BKV_SMALL = 64;
+template <int DH>
+void run_attn(const AttnArgs& a, hipStream_t st) {
+    if (a.L > 128) run_attn_cfg<DH, 256, 128, 512>(a, st);
+    else run_attn_cfg<DH, 128, BKV_SMALL, 256>(a, st);
 }
 
 }  // namespace
@@ -353,7 +364,7 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
     a.nsplit = 1;
     a.part = scratch;
     if (L == 1 && scratch) {
-        const int tiles = (P + L - 1) / BKV + 1;
+        const int tiles = (P + L - 1) / BKV_SMALL + 1;
         int ns = 1024 / (B * n_heads);
         ns = ns > MAX_SPLIT ? MAX_SPLIT : ns;
         ns = ns > tiles ? tiles : ns;
