@@ -1,0 +1,116 @@
+"""The throughput-sweep workload (7B-class decoder, 64x64 grid, batch 16, draft
+blocks of 256 / 512 / 1024 tokens, draft-logit noise sigma in {0.5, 1, 2}) at its
+full launch shapes through mulo_verify_step.
+
+The oracle cannot recompute a 16 x 1024-token 7B forward (hours of float64), so
+the forward is checked by what holds at any size: a sequence of the batched
+launch equals the same sequence launched alone (sequences are independent), whose
+per-sequence shapes (P = 3200 .. 3968, L = 256 .. 1024) the single-sequence
+oracle comparisons of test_gpu_forward.py cover.  The decision stage is compared
+with the oracle on the device's own logits: the whole batch at L = 256 for every
+sigma, the first two sequences at L = 512 and 1024."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_05149_amd as mulo
+from oracle import step as ST
+from oracle import upsample as UP
+from tests.gpu_util import DEV, compare_decisions, decide_buffers, make_ctx, say, to_np
+from tests.test_gpu_forward import weights_7b
+from workloads import configs as WC
+
+pytestmark = pytest.mark.gpu
+
+
+def draft_like_target(ctx, kv, c, P, sigma, gen):
+    """The benchmark's draft recipe: a provisional uniform draft is up-sampled and
+    run through the target once; the draft logits of a low-resolution cell are the
+    target logits of its top-left child + sigma * N(0, 1); draft tokens are drawn
+    from softmax(draft logits)."""
+    B, L, V, r = c["B"], c["L"], c["model"]["vocab"], c["r"]
+    h_blk = L // c["W"] // r
+    n_lo = h_blk * c["w"]
+    prov = torch.randint(0, V, (B, n_lo), generator=gen, device=DEV, dtype=torch.int32)
+    thi = torch.empty(B, L, dtype=torch.int32, device=DEV)
+    q_lo = torch.empty(B, n_lo, V, device=DEV)
+    q_row = torch.empty(L, dtype=torch.int32, device=DEV)
+    mulo.mulo_upsample_draft(ctx, B, h_blk, c["w"], r, torch.zeros(B, n_lo, V, device=DEV), 0, prov, thi, q_lo, q_row,
+                             None)
+    prev = torch.randint(0, V, (B,), generator=gen, device=DEV, dtype=torch.int32)
+    inp = torch.cat([prev.reshape(B, 1), thi[:, :L - 1]], dim=1).contiguous()
+    zp = torch.empty(B, L, V, device=DEV)
+    mulo.mulo_verify_forward(ctx, kv, B, L, P, inp, None, zp)
+    child0 = (torch.arange(h_blk, device=DEV)[:, None] * r * c["W"]
+              + torch.arange(c["w"], device=DEV)[None, :] * r).reshape(-1)
+    dl = (zp[:, child0, :] + sigma * torch.randn(B, n_lo, V, generator=gen, device=DEV)).contiguous()
+    gumbel = -torch.log(-torch.log(torch.rand(B, n_lo, V, generator=gen, device=DEV).clamp_min(1e-20)))
+    dt = (dl + gumbel).argmax(-1).to(torch.int32).contiguous()
+    return dl, dt, prev
+
+
+@pytest.mark.timeout(1500)
+def test_sweep_full_launches_decisions_and_sequence_independence():
+    w = weights_7b()
+    c0 = WC.get("cfg5_L1024")
+    m, B, S = c0["model"], c0["B"], c0["max_seq"]
+    V = m["vocab"]
+    ctx, _, _ = make_ctx(m, w, B, S, 1024)
+    ctx1, _, _ = make_ctx(m, w, 1, S, 1024)
+    kv = mulo.alloc_kv(ctx, DEV)
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    # cache rows of the prefix and the committed blocks: seeded N(0, 1) values (a real prefill is hours of oracle time)
+    kv[0][:, :, :, :S - 256].normal_(generator=gen)
+    kv[1][:, :, :, :, :S - 256].normal_(generator=gen)
+    for L in (256, 512, 1024):
+        c = WC.get("cfg5_L%d" % L)
+        P, n0, r = S - L, c["T"] - L, c["r"]
+        h_blk = L // c["W"] // r
+        rates = []
+        for si, sigma in enumerate((0.5, 1.0, 2.0)):
+            if L != 256 and sigma != 1.0:
+                continue
+            say("sweep L=%d sigma=%.1f: launch B=%d ..." % (L, sigma, B))
+            dl, dt, prev = draft_like_target(ctx, kv, c, P, sigma, gen)
+            out = decide_buffers(B, L)
+            thi = torch.empty(B, L, dtype=torch.int32, device=DEV)
+            logits = torch.empty(B, L, V, device=DEV)
+            params = mulo.make_params(c["H"], c["W"], n0, L, c["radius"], c["expand"], seed=7, rng_counter=10 * L + si)
+            mulo.mulo_verify_step(ctx, kv, B, P, params, h_blk, c["w"], r, dl, 0, dt, prev, out["tokens_out"],
+                                  out["accept"], out["mask"], out["t0"], out["stats"], thi, logits)
+            torch.cuda.synchronize()
+            assert torch.isfinite(logits).all()
+            got = to_np(out)
+            nb = B if L == 256 else 2      # sequences the oracle re-decides (Philox words are indexed by (t, b))
+            dl_n, dt_n = dl[:nb].cpu().numpy(), dt[:nb].cpu().numpy()
+            tokens_hi, q_lo, q_row, _ = UP.upsample_draft(dl_n, dt_n, h_blk, c["w"], r)
+            assert np.array_equal(tokens_hi, thi[:nb].cpu().numpy())
+            ref = ST.decide(logits[:nb].cpu().numpy(), q_lo, q_row, tokens_hi, W=c["W"], n0=n0, radius=c["radius"],
+                            expand=c["expand"], seed=7, rng_counter=10 * L + si)
+            rep = compare_decisions({k: v[:nb] for k, v in got.items()}, ref, tokens_hi, q_lo, q_row,
+                                    label="sweep L=%d sigma=%.1f" % (L, sigma))
+            acc = float(got["stats"][:, 0].sum()) / (B * L)
+            rates.append(acc)
+            say("  acceptance %.3f, marked %.3f, %r" % (acc, got["mask"].mean(), rep))
+            assert rep["sequences_checked"] >= nb - 1
+            # untouched positions keep the draft token; counts add up in every sequence of the batch
+            keep = got["mask"] == 0
+            assert np.array_equal(got["tokens_out"][keep], thi.cpu().numpy()[keep])
+            assert np.array_equal(got["stats"][:, 0] + got["stats"][:, 1], np.full(B, L))
+            assert np.array_equal(got["stats"][:, 2], got["mask"].sum(1))
+            if sigma == 1.0:
+                # the last sequence alone (its own context, cache and workspace) reproduces its rows of the batch
+                b = B - 1
+                kv1 = (kv[0][:, b:b + 1].contiguous(), kv[1][:, b:b + 1].contiguous())
+                inp = torch.cat([prev[b:b + 1].reshape(1, 1), thi[b:b + 1, :L - 1]], dim=1).contiguous()
+                z1 = torch.empty(1, L, V, device=DEV)
+                mulo.mulo_verify_forward(ctx1, kv1, 1, L, P, inp, None, z1)
+                torch.cuda.synchronize()
+                dmax = float((z1 - logits[b:b + 1]).abs().max())
+                say("  sequence %d alone vs in the batch: max |diff| %.3g" % (b, dmax))
+                assert dmax <= 1e-3
+                del kv1, z1
+            del dl, dt, logits, thi
+        if len(rates) == 3:     # more draft noise, fewer accepted tokens
+            assert rates[0] > rates[1] > rates[2], rates
+    del ctx, ctx1, kv
