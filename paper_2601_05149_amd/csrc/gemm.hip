@@ -125,6 +125,54 @@ template <int EPI, int BN, int TM, int TN, int MB, int NB>
 __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB], int m0, int n0, int tile_n,
                                          int wm, int wn, int l32, int lh) {
     constexpr int NBE = EPI == EPI_SWIGLU ? NB / 2 : NB;   // gate blocks only: up blocks are consumed with them
+    if constexpr (EPI == EPI_RESID) {
+        // x += acc.  The compiler cannot tell the stream's loads from its stores, so a plain read-add-write per
+        // run is a chain of MB * NB * 2 memory round trips per lane (about a microsecond each: the whole
+        // epilogue of a launch with one tile per CU).  All runs of one block row are requested first, then
+        // added and written: two round trips per lane.
+        static_for<MB>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const int m = m0 + wm * TM + i * 32 + l32;
+            if (m < g.M) {
+                float* const row = g.Cf + (int64_t)m * g.N + n0 + wn * TN + lh * 8;
+                const int nrow = n0 + wn * TN + lh * 8;
+                f32x4 r[NB][2][2];
+                static_for<NB>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+#pragma unroll
+                    for (int g2 = 0; g2 < 2; ++g2) {
+                        const int cl = j * 32 + g2 * 16;
+                        if (nrow + cl + 8 <= g.N) {
+                            r[j][g2][0] = *reinterpret_cast<const f32x4*>(row + cl);
+                            r[j][g2][1] = *reinterpret_cast<const f32x4*>(row + cl + 4);
+                        }
+                    }
+                });
+                static_for<NB>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+#pragma unroll
+                    for (int g2 = 0; g2 < 2; ++g2) {
+                        const int cl = j * 32 + g2 * 16;
+                        if (nrow + cl + 8 <= g.N) {
+                            f32x4 lo, hi;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                lo[e] = r[j][g2][0][e] + acc[i][j][g2 * 8 + e];
+                                hi[e] = r[j][g2][1][e] + acc[i][j][g2 * 8 + 4 + e];
+                            }
+                            *reinterpret_cast<f32x4*>(row + cl) = lo;
+                            *reinterpret_cast<f32x4*>(row + cl + 4) = hi;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (nrow + cl + e < g.N) row[cl + e] += acc[i][j][g2 * 8 + e];
+                        }
+                    }
+                });
+            }
+        });
+        return;
+    }
     static_for<MB>([&](auto ic) {
         static_for<NBE>([&](auto jc) {
             constexpr int i = decltype(ic)::value, j = decltype(jc)::value;
