@@ -548,85 +548,113 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 
 
 // ---- up to 32 tokens (single-token decoding of a few sequences): weight-streaming kernel ------------
-// The work is reading every weight once, so nothing is staged: a workgroup owns 32 output columns (for
-// gate|up: 32 feed-forward columns = 32 gate rows + 32 up rows), its 8 wavefronts split K, and every lane
-// feeds MFMAs straight from global memory.  The k-slices of a 64-deep block are dealt so that a lane reads
-// 64 contiguous bytes of one weight row (lane half lh owns k in [32 lh, 32 lh + 32) of the block; MFMA step
-// j takes its j-th 16 bytes, the token operand follows the same deal), i.e. a wavefront reads whole 128-byte
-// lines of 32 rows.  The tokens are the MFMA's lane dimension (lanes m >= M contribute zeros and issue no
-// loads), so the accumulators come out as D[column][token] like in the tiled kernel; the 8 partial sums are
-// added in a fixed order through LDS and 512 threads apply the epilogue to pairs of adjacent columns.
-template <int EPI>
+// The work is reading every weight once, so nothing is staged: a workgroup owns 16 output columns (for
+// gate|up: 16 feed-forward columns = 16 gate rows + 16 up rows), its 8 wavefronts split K, and every lane
+// feeds v_mfma_f32_16x16x32_bf16 straight from global memory.  In that instruction's operand layout the four
+// lanes l16, l16 + 16, l16 + 32, l16 + 48 hold 4 x 8 consecutive k of weight row l16, so one load instruction
+// of a wavefront reads 64 contiguous bytes of each of 16 rows: whole 64-byte sectors (with the 32-row
+// instruction only two lanes share a row, 32 of every 64 bytes fetched per request), and a matrix of N columns
+// gives N / 16 workgroups (256 for the 4096-column projections: one per CU).  The tokens are the instruction's
+// column dimension (columns m >= M are fed zeros), up to two groups of 16; the accumulators come out as
+// D[weight row 4 q + i][token l16], q = lane / 16: a lane owns 4 consecutive output columns of one token.  The
+// 8 partial sums are added in a fixed order through LDS and the epilogue runs on pairs of adjacent columns.
+typedef __attribute__((ext_vector_type(4))) float f32x4v;
+template <int EPI, int MT>
 __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
-    __shared__ float part[8][16][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
-    const int n_blk = blockIdx.x * 32;     // first output column (gate|up: first feed-forward column)
-    const int nblk = g.K / 64, per = (nblk + 7) / 8;
-    const int kb0 = wave * per, kb1 = kb0 + per < nblk ? kb0 + per : nblk;
+    constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;   // weight matrices (accumulator sets) per column
+    constexpr int U = 8;                            // 32-deep k-steps requested together
+    __shared__ float part[8][NA * MT][4][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, q = lane >> 4;
+    const int n_blk = blockIdx.x * 16;     // first output column (gate|up: first feed-forward column)
+    const int steps = g.K / 32, per = (steps + 7) / 8;
+    const int s0 = wave * per, s1 = s0 + per < steps ? s0 + per : steps;
 
     // weight row(s) of this lane
-    const bf16* w0;
-    const bf16* w1 = nullptr;
+    const bf16* w[NA];
     {
-        int r = n_blk + l32;
+        int r = n_blk + l16;
         if constexpr (EPI == EPI_QK) {
-            const int seg = n_blk / g.d;                       // a block never straddles q | k (d % 32 == 0)
-            w0 = (seg == 0 ? g.W0 : g.W1) + (int64_t)(r - seg * g.d) * g.K;
+            const int seg = n_blk / g.d;                       // a block never straddles q | k (d % 16 == 0)
+            w[0] = (seg == 0 ? g.W0 : g.W1) + (int64_t)(r - seg * g.d) * g.K;
         } else if constexpr (EPI == EPI_SWIGLU) {
             const int f = g.N / 2;
             r = r < f ? r : f - 1;
-            w0 = g.W0 + (int64_t)r * g.K;
-            w1 = g.W1 + (int64_t)r * g.K;
+            w[0] = g.W0 + (int64_t)r * g.K;
+            w[1] = g.W1 + (int64_t)r * g.K;
         } else {
             r = r < g.N ? r : g.N - 1;
-            w0 = g.W0 + (int64_t)r * g.K;
+            w[0] = g.W0 + (int64_t)r * g.K;
         }
     }
-    const bool has_x = l32 < g.M;
-    const bf16* xp = g.A + (int64_t)(has_x ? l32 : 0) * g.K + lh * 32;
-    w0 += lh * 32;
-    if constexpr (EPI == EPI_SWIGLU) w1 += lh * 32;
+    // token row(s) of this lane: lanes past M read token 0's row and feed zeros
+    const bf16* xp[MT];
+    bool has_x[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        has_x[t] = t * 16 + l16 < g.M;
+        xp[t] = g.A + (int64_t)(has_x[t] ? t * 16 + l16 : 0) * g.K + q * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < NA; ++i) w[i] += q * 8;
 
-    f32x16 acc0, acc1;
+    f32x4v acc[NA][MT];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[i][t] = f32x4v{0.f, 0.f, 0.f, 0.f};
     const u32x4 zero = {0u, 0u, 0u, 0u};
-    for (int kb = kb0; kb < kb1; ++kb) {
-        u32x4 wa[4], wb[4], xv[4];
+    // U steps at a time, free of branches (steps past the end of the slice re-read the last step and are
+    // multiplied by zeros), so that all their loads are in flight before the first MFMA waits
+    for (int sb = s0; sb < s1; sb += U) {
+        u32x4 wv[NA][U], xv[MT][U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wa[j] = *reinterpret_cast<const u32x4*>(w0 + kb * 64 + j * 8);
-        if constexpr (EPI == EPI_SWIGLU) {
+        for (int u = 0; u < U; ++u) {
+            const int sc = sb + u < steps ? sb + u : steps - 1;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wb[j] = *reinterpret_cast<const u32x4*>(w1 + kb * 64 + j * 8);
+            for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * 32);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) xv[t][u] = *reinterpret_cast<const u32x4*>(xp[t] + sc * 32);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xv[j] = has_x ? *reinterpret_cast<const u32x4*>(xp + kb * 64 + j * 8) : zero;
+        for (int u = 0; u < U; ++u) {
+            const bool in_slice = sb + u < s1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[j]);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa[j]), xf, acc0, 0, 0, 0);
-            if constexpr (EPI == EPI_SWIGLU)
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wb[j]), xf, acc1, 0, 0, 0);
+            for (int t = 0; t < MT; ++t) {
+                const bf16x8 xf = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xv[t][u] : zero);
+#pragma unroll
+                for (int i = 0; i < NA; ++i)
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[i][u]), xf,
+                                                                        acc[i][t], 0, 0, 0);
+            }
         }
     }
-    // reduce the K-slices: thread (rp, lane) owns accumulators 2 rp, 2 rp + 1 = two adjacent columns of token l32
-    const int rp = wave;
-    float v0[2] = {0.f, 0.f}, v1[2] = {0.f, 0.f};
-    for (int pass = 0; pass < (EPI == EPI_SWIGLU ? 2 : 1); ++pass) {
-        if (pass) __syncthreads();
+    // reduce the K-slices in a fixed order; thread (pr, t, lane) of the first 2 * MT wavefronts then owns
+    // accumulators 2 pr, 2 pr + 1 of token group t = two adjacent columns of token t * 16 + l16
 #pragma unroll
-        for (int r = 0; r < 16; ++r) part[wave][r][lane] = pass ? acc1[r] : acc0[r];
-        __syncthreads();
-        float s0 = 0.f, s1 = 0.f;
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
-        for (int w = 0; w < 8; ++w) { s0 += part[w][2 * rp][lane]; s1 += part[w][2 * rp + 1][lane]; }
-        if (pass) { v1[0] = s0; v1[1] = s1; } else { v0[0] = s0; v0[1] = s1; }
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[wave][i * MT + t][r][lane] = acc[i][t][r];
+    __syncthreads();
+    if (wave >= 2 * MT) return;
+    const int pr = wave & 1, tg = wave >> 1;
+    float v0[2], v1[2] = {0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 8; ++ww) {
+            sum0 += part[ww][tg][2 * pr + e][lane];
+            if constexpr (EPI == EPI_SWIGLU) sum1 += part[ww][MT + tg][2 * pr + e][lane];
+        }
+        v0[e] = sum0;
+        v1[e] = sum1;
     }
-    if (!has_x) return;
-    const int m = l32;
-    // accumulator r of a lane is column (r / 4) * 8 + lh * 4 + r % 4 of the block
-    const int col = ((2 * rp) / 4) * 8 + lh * 4 + (2 * rp) % 4;
-    const int n = n_blk + col;
+    const int m = tg * 16 + l16;
+    if (m >= g.M) return;
+    const int n = n_blk + 4 * q + 2 * pr;
     if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
         float* dst = g.Cf + (int64_t)m * g.N + n;
 #pragma unroll
@@ -667,7 +695,8 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
 template <int EPI>
 void run_gemv(const GemmArgs& g, hipStream_t st) {
     const int cols = EPI == EPI_SWIGLU ? g.N / 2 : g.N;
-    hipLaunchKernelGGL(k_gemv_bf16<EPI>, dim3((cols + 31) / 32), dim3(512), 0, st, g);
+    if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1>), dim3((cols + 15) / 16), dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((k_gemv_bf16<EPI, 2>), dim3((cols + 15) / 16), dim3(512), 0, st, g);
 }
 
 template <int EPI>
