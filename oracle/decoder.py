@@ -130,3 +130,53 @@ class DecoderOracle:
             x = x + hmid @ self._w("w_down", l).T
         xh = self.rb(rmsnorm(x, self._w("final_norm"), eps))
         return xh @ self._w("lm_head").T
+
+    @torch.no_grad()
+    def forward_at(self, tokens, seq, pos, visible):
+        """One pass of M_p over single-token queries at scattered cache rows (island-parallel re-sampling,
+        Sec. 3.4: positions of different rejection islands are evaluated concurrently).
+
+        tokens: int [n] input token of each query; seq: int [n] the cache sequence it belongs to; pos: int [n]
+        its cache row (its rotary position); visible: bool [n, S], S > max(pos): the cache rows query i attends
+        to (row pos[i] itself must be among them).  At every layer all queries first write their own k, v to
+        cache row (seq[i], pos[i]), then each attends to its visible rows of its sequence.  Returns float64
+        logits [n, V]: row i is the distribution of the token at block position pos[i] + 1 - (rows before the
+        block), i.e. of the token that follows input i."""
+        cfg = self.cfg
+        nl, d, nh, dh = cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
+        eps = cfg.get("rms_eps", 1e-5)
+        tok = torch.as_tensor(np.asarray(tokens)).long().reshape(-1)
+        seq = [int(b) for b in np.asarray(seq).reshape(-1)]
+        pos = [int(r) for r in np.asarray(pos).reshape(-1)]
+        vis = torch.as_tensor(np.asarray(visible)).bool()
+        n, S = vis.shape
+        assert len(seq) == n and len(pos) == n and all(vis[i, pos[i]] for i in range(n))
+        x = self._w("embed")[tok]                                           # [n, d]
+        cos, sin = self.cos[pos], self.sin[pos]                             # [n, dh/2]
+        for l in range(nl):
+            xh = self.rb(rmsnorm(x, self._w("attn_norm", l), eps))
+            q = (xh @ self._w("wq", l).T).reshape(1, n, nh, dh)
+            k = (xh @ self._w("wk", l).T).reshape(1, n, nh, dh)
+            v = (xh @ self._w("wv", l).T).reshape(n, nh, dh)
+            q = self.rb(rotary(q, cos, sin))[0]
+            k = self.rb(rotary(k, cos, sin))[0]
+            v = self.rb(v)
+            for i in range(n):
+                self.k[l, seq[i], pos[i]] = k[i].to(self.k.dtype)
+                self.v[l, seq[i], pos[i]] = v[i].to(self.v.dtype)
+            a = torch.empty(n, nh, dh, dtype=torch.float64)
+            for i in range(n):
+                K = self.k[l, seq[i], :S].to(torch.float64)                 # [S, nh, dh]
+                Vv = self.v[l, seq[i], :S].to(torch.float64)
+                s = torch.einsum("hc,shc->hs", q[i], K) / math.sqrt(dh)     # [nh, S]
+                s = s.masked_fill(~vis[i][None, :], float("-inf"))
+                s = s - s.max(dim=-1, keepdim=True).values
+                e = torch.exp(s)
+                a[i] = torch.einsum("hs,shc->hc", e / e.sum(dim=-1, keepdim=True), Vv)
+            a = self.rb(a.reshape(n, d))
+            x = x + a @ self._w("wo", l).T
+            xh = self.rb(rmsnorm(x, self._w("ffn_norm", l), eps))
+            hmid = self.rb(silu(xh @ self._w("w_gate", l).T) * (xh @ self._w("w_up", l).T))
+            x = x + hmid @ self._w("w_down", l).T
+        xh = self.rb(rmsnorm(x, self._w("final_norm"), eps))
+        return xh @ self._w("lm_head").T

@@ -113,3 +113,47 @@ def resample_sequential(decoder, P, tokens, mask, t0, prev_tokens, *, seed=0, rn
     if logits is None:
         logits = np.zeros((B, L, 0))
     return tok, logits
+
+
+def resample_islands(decoder, P, tokens, mask, rank, prev_tokens, *, seed=0, rng_counter=0):
+    """Island-parallel re-sampling (Sec. 3.4): the rejection islands of Eq. 8 are re-sampled concurrently,
+    the positions inside an island one after the other in raster order.  Pass r evaluates, in ONE target
+    call, the position of rank r of every island that has one, and draws its token from the target model.
+
+    The paper does not spell out the context of such a concurrent evaluation; the reading taken here follows
+    its statement that the accepted tokens are a valid and sufficient context: the query at block position u
+    attends to the prefix and to those earlier block positions that are settled -- accepted ones (their cache
+    rows are the verification pass's) and marked ones re-drawn in an earlier pass (rows rewritten then) --
+    and to itself; marked positions not yet re-drawn are hidden.  Its input is the current token at u - 1.
+    Its k, v replace cache row P + u.  Draws use the integer inverse CDF of p with the Philox word of the
+    sequential stream at (position, batch element), so one island covering everything from its first
+    position on is exactly `resample_sequential`.
+
+    decoder: oracle decoder whose rows [0, P) are valid and whose rows P .. P+L-1 hold the verification pass
+    of the block; tokens: int [B, L]; mask: [B, L] = R_X; rank: int [B, L] from local.rejection_islands
+    (-1 where unmarked); prev_tokens: [B].  Returns (tokens_out int32 [B, L], passes, logits {(b, u): row})."""
+    tok = np.asarray(tokens).astype(np.int32).copy()
+    mask = np.asarray(mask).astype(bool)
+    rank = np.asarray(rank)
+    B, L = tok.shape
+    words = PH.step_words(seed, rng_counter, PH.STREAM_SEQUENTIAL, B, L)
+    settled = ~mask                                   # positions whose token and cache row are final
+    passes = 0
+    rows = {}
+    while not settled.all():
+        sel = [(b, u) for b in range(B) for u in range(L) if mask[b, u] and rank[b, u] == passes]
+        assert sel, "ranks must be consecutive inside every island"
+        inp = [int(np.asarray(prev_tokens)[b]) if u == 0 else int(tok[b, u - 1]) for b, u in sel]
+        vis = np.zeros((len(sel), P + L), dtype=bool)
+        for i, (b, u) in enumerate(sel):
+            vis[i, :P] = True
+            vis[i, P:P + u] = settled[b, :u]
+            vis[i, P + u] = True
+        z = decoder.forward_at(inp, [b for b, _ in sel], [P + u for _, u in sel], vis).numpy()
+        for i, (b, u) in enumerate(sel):
+            tok[b, u] = RS.draw(RS.integer_weights(A.target_probs(z[i])), words[b, u])
+            rows[(b, u)] = z[i]
+        for b, u in sel:
+            settled[b, u] = True
+        passes += 1
+    return tok, passes, rows

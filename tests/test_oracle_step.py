@@ -1,6 +1,7 @@
 """The oracle's whole verification step on the Tiny workload: invariants that
 tie the stages together.  CPU only."""
 import numpy as np
+import torch
 
 from oracle import accept as A
 from oracle import decoder as D
@@ -127,3 +128,128 @@ def test_sequential_resampling_with_nothing_marked_is_the_identity():
     dec = mk(); dec.forward(prefix[:, :-1], 0)
     out, _ = ST.resample_sequential(dec, Pn - 1, draft, np.zeros((B, L), bool), np.array([L, L]), prefix[:, -1])
     assert np.array_equal(out, draft)
+
+
+# --------------------------------------------------------------- island-parallel re-sampling (Sec. 3.4)
+def _island_setup(B, Pn, H, W, seed):
+    """Prefix prefilled without its last token, then the verification pass over the drafted H x W block."""
+    m, mk = _seq_setup()
+    V, L = m["vocab"], H * W
+    prefix = G.uniform_tokens((B, Pn), V, seed, tag=0)
+    draft = G.uniform_tokens((B, L), V, seed + 1, tag=0)
+    dec = mk(); dec.forward(prefix[:, :-1], 0)
+    dec.forward(np.concatenate([prefix[:, -1:], draft[:, :-1]], axis=1), Pn - 1)
+    return m, mk, prefix, draft, dec
+
+
+def _ranks(mask, W):
+    from oracle import local as LOC
+    out = [LOC.rejection_islands(mk_, W, 0) for mk_ in mask]
+    return np.stack([o[1] for o in out]), max(o[3] for o in out)
+
+
+def test_forward_at_on_a_contiguous_causal_block_is_the_block_pass():
+    """Scattered queries at consecutive rows with causal visibility are the ordinary pass over a block: the
+    library-style batched forward and the per-query forward agree in logits and in the cache they leave."""
+    m, mk = _seq_setup()
+    B, Pn, L = 2, 5, 7
+    toks = G.uniform_tokens((B, Pn + L), m["vocab"], 8, tag=0)
+    a, b = mk(), mk()
+    a.forward(toks[:, :Pn], 0); b.forward(toks[:, :Pn], 0)
+    za = a.forward(toks[:, Pn:], Pn).numpy()
+    # the same L rows per sequence as single-token queries (all written first, each sees rows <= its own)
+    seq = [s for s in range(B) for _ in range(L)]
+    pos = [Pn + j for _ in range(B) for j in range(L)]
+    vis = np.zeros((B * L, Pn + L), bool)
+    for i, r in enumerate(pos):
+        vis[i, :r + 1] = True
+    zb = b.forward_at(toks[:, Pn:].reshape(-1), seq, pos, vis).numpy().reshape(B, L, -1)
+    assert np.abs(za - zb).max() < 1e-10
+    assert np.allclose(a.k.numpy(), b.k.numpy(), atol=1e-12) and np.allclose(a.v.numpy(), b.v.numpy(), atol=1e-12)
+    # hiding a row changes the result (the visibility argument is used)
+    vis2 = vis.copy(); vis2[L - 1, Pn] = False
+    assert np.abs(b.forward_at(toks[:, Pn:].reshape(-1), seq, pos, vis2).numpy()[L - 1] - za[0, L - 1]).max() > 1e-3
+
+
+def test_one_island_from_t0_on_is_sequential_resampling():
+    """Everything from t0 on marked = one island whose ranks are the raster order: the island-parallel scheme
+    degenerates to Alg. 1 Step 6 (same tokens, same cache), which is pinned above as ancestral sampling."""
+    B, Pn, H, W = 2, 4, 3, 4
+    m, mk, prefix, draft, dec = _island_setup(B, Pn, H, W, seed=11)
+    L = H * W
+    t0 = np.array([2, 5])
+    mask = np.arange(L)[None, :] >= t0[:, None]
+    rank, largest = _ranks(mask, W)
+    assert np.array_equal(rank[0, 2:], np.arange(L - 2)) and largest == L - 2
+    out, passes, rows = ST.resample_islands(dec, Pn - 1, draft, mask, rank, prefix[:, -1], seed=3, rng_counter=2)
+    m2, mk2, _, _, dec2 = _island_setup(B, Pn, H, W, seed=11)
+    ref, zs = ST.resample_sequential(dec2, Pn - 1, draft, mask, t0, prefix[:, -1], seed=3, rng_counter=2)
+    assert passes == largest and np.array_equal(out, ref)
+    for b in range(B):      # cache rows from each sequence's t0 on were rewritten identically
+        lo = Pn - 1 + t0[b]
+        assert np.allclose(dec.k[:, b, lo:Pn - 1 + L].numpy(), dec2.k[:, b, lo:Pn - 1 + L].numpy(), atol=1e-9)
+    for (b, u), z in rows.items():
+        assert np.abs(z - zs[b, u]).max() < 1e-9
+
+
+def test_islands_are_resampled_concurrently_and_see_only_settled_positions():
+    B, Pn, H, W = 2, 4, 6, 6
+    m, mk, prefix, draft, dec = _island_setup(B, Pn, H, W, seed=21)
+    L, P = H * W, Pn - 1
+    mask = np.zeros((B, L), bool)
+    mask[0, [1, 2, 8]] = True          # island {1, 2, 8} (8 = row 1, col 2 touches 1 and 2 diagonally / vertically)
+    mask[0, [22, 23, 29]] = True       # island {22, 23, 29}, far from the first
+    mask[0, 33] = True                 # a single position
+    mask[1, [6, 12, 18]] = True        # a vertical island in column 0
+    mask[1, 11] = True                 # row 1, last column: raster neighbour of 12 but not a grid neighbour
+    rank, largest = _ranks(mask, W)
+    assert largest == 3 and rank[1, 11] == 0 and rank[1, 12] == 1
+    calls = []
+    orig = dec.forward_at
+    dec.forward_at = lambda t, s, p, v: (calls.append((list(s), list(p), np.array(v))), orig(t, s, p, v))[1]
+    out, passes, rows = ST.resample_islands(dec, P, draft, mask, rank, prefix[:, -1], seed=6, rng_counter=1)
+    # one target call per rank, each holding one position of every island that still has one
+    assert passes == 3 and [len(c[0]) for c in calls] == [5, 3, 3]
+    assert np.array_equal(out[~mask], draft[~mask])
+    # visibility, restated from the ranks: hidden = marked, not the query itself, rank >= pass
+    for r, (seqs, rows_, vis) in enumerate(calls):
+        for i, (b, row) in enumerate(zip(seqs, rows_)):
+            u = row - P
+            want = np.zeros(P + L, bool)
+            want[:P] = True
+            for v in range(u + 1):
+                want[P + v] = v == u or not mask[b, v] or rank[b, v] < r
+            assert np.array_equal(vis[i], want)
+    # every draw is the inverse-CDF draw from the row the pass produced, with the sequential stream's word
+    words = PH.step_words(6, 1, PH.STREAM_SEQUENTIAL, B, L)
+    for (b, u), z in rows.items():
+        assert out[b, u] == RS.draw(RS.integer_weights(A.target_probs(z)), words[b, u])
+    # what the cache held at marked positions before the call never reaches a result: every such row is
+    # rewritten before anything may attend to it
+    m3, mk3, _, _, dec3 = _island_setup(B, Pn, H, W, seed=21)
+    rng = np.random.default_rng(0)
+    for b, u in zip(*np.nonzero(mask)):
+        dec3.k[:, b, P + u] = torch.tensor(rng.normal(size=dec3.k[:, b, P + u].shape))
+        dec3.v[:, b, P + u] = torch.tensor(rng.normal(size=dec3.v[:, b, P + u].shape))
+    out3, _, rows3 = ST.resample_islands(dec3, P, draft, mask, rank, prefix[:, -1], seed=6, rng_counter=1)
+    assert np.array_equal(out3, out) and max(np.abs(rows3[k] - rows[k]).max() for k in rows) < 1e-9
+    # ... whereas an accepted position's row does (hiding too much would pass the line above)
+    m4, mk4, _, _, dec4 = _island_setup(B, Pn, H, W, seed=21)
+    dec4.k[:, 0, P + 0] += 1.0
+    _, _, rows4 = ST.resample_islands(dec4, P, draft, mask, rank, prefix[:, -1], seed=6, rng_counter=1)
+    assert np.abs(rows4[(0, 1)] - rows[(0, 1)]).max() > 1e-3
+    # a later position of an island sees the earlier re-draw: its row is the conditional given the NEW token
+    # (position 2 follows position 1 in island one: changing the word that drew 1 changes the row at 2)
+    m5, mk5, _, _, dec5 = _island_setup(B, Pn, H, W, seed=21)
+    out5, _, rows5 = ST.resample_islands(dec5, P, draft, mask, rank, prefix[:, -1], seed=7, rng_counter=1)
+    if out5[0, 1] != out[0, 1]:
+        assert np.abs(rows5[(0, 2)] - rows[(0, 2)]).max() > 1e-3
+
+
+def test_island_resampling_with_nothing_marked_is_the_identity():
+    B, Pn, H, W = 2, 4, 2, 3
+    m, mk, prefix, draft, dec = _island_setup(B, Pn, H, W, seed=31)
+    mask = np.zeros((B, H * W), bool)
+    rank, largest = _ranks(mask, W)
+    out, passes, rows = ST.resample_islands(dec, Pn - 1, draft, mask, rank, prefix[:, -1])
+    assert passes == 0 and largest == 0 and not rows and np.array_equal(out, draft)
