@@ -244,6 +244,33 @@ MULO_API mulo_status mulo_resample_sequential(mulo_ctx *ctx, mulo_kv *kv, int32_
 MULO_API mulo_status mulo_rejection_islands(mulo_ctx *ctx, int32_t B, int32_t W, int32_t n0, int32_t L,
                                    const uint8_t *mask, int32_t *island, int32_t *rank, int32_t *counts);
 
+/* Island-parallel re-sampling (Sec. 3.4, "Parallel resampling via rejection islands"): the islands of R_X are
+ * re-sampled concurrently, the positions inside an island one after the other in raster order.  Pass r
+ * (r = 0 .. n_passes-1) evaluates the target ONCE on the rank-r position of every island that has one (a batch of
+ * single-token queries at scattered cache rows) and replaces tokens[b,u] of each by a draw from softmax of its
+ * logit row (integer inverse CDF, Philox stream 2 at (u, b), as in mulo_resample_sequential).  The query at block
+ * position u takes the current token at u-1 as input (prev_tokens[b] for u = 0), rewrites cache row P+u in every
+ * layer and attends to rows [0, P), to its own row, and to the earlier rows P+v of its block whose position is
+ * settled: not marked (the verification pass's row) or re-drawn in an earlier pass.  Marked positions not yet
+ * re-drawn are hidden.  (Which context a concurrently evaluated position may use is not spelled out by the paper;
+ * this is the reading "the accepted tokens are a valid and sufficient context".)  One island that covers everything
+ * from its first position on gives exactly mulo_resample_sequential.  The cache rows P .. P+L-1 must hold the
+ * verification pass over the block.  bf16 models only.
+ *   n_passes    size of the largest island over the batch, max_islands >= the largest number of islands of a
+ *               sequence: both from counts of mulo_rejection_islands (host values; upper bounds are fine);
+ *               B * max_islands <= max_batch * max_block
+ *   prev_tokens device int32 [B]; mask device uint8 [B, L]; rank device int32 [B, L] (mulo_rejection_islands)
+ *   tokens      device int32 [B, L] (in/out)
+ *   logits      device float32 [B, L, vocab] (out) or NULL: the logit row of every re-drawn position
+ *   overflow    device int32 [1] or NULL: incremented by the number of positions a pass could not place because
+ *               max_islands was too small (they are then not re-drawn); the caller zeroes it
+ * Nothing synchronises with the host.  Errors: as mulo_resample_sequential; float32 model ->
+ * MULO_ERR_UNSUPPORTED; B * max_islands too large -> MULO_ERR_SHAPE. */
+MULO_API mulo_status mulo_resample_islands(mulo_ctx *ctx, mulo_kv *kv, int32_t B, int32_t P, int32_t L,
+                                  int32_t n_passes, int32_t max_islands, uint64_t seed, uint64_t rng_counter,
+                                  const int32_t *prev_tokens, const uint8_t *mask, const int32_t *rank,
+                                  int32_t *tokens, float *logits, int32_t *overflow);
+
 /* Optional per-kernel timing (measurement aid, not part of the method).  While
  * enabled, every kernel launch of the entry points above is bracketed by a pair
  * of HIP events on the context's stream.  mulo_profile_read synchronises the

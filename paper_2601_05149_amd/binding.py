@@ -17,7 +17,7 @@ STATUS_NAMES = {0: "MULO_OK", 1: "MULO_ERR_NULL", 2: "MULO_ERR_SHAPE", 3: "MULO_
                 4: "MULO_ERR_ALLOC", 5: "MULO_ERR_HIP", 6: "MULO_ERR_UNSUPPORTED"}
 EXPORTS = ["mulo_status_string", "mulo_check_model_cfg", "mulo_check_step_params", "mulo_workspace_bytes",
            "mulo_create", "mulo_destroy", "mulo_upsample_draft", "mulo_verify_forward",
-           "mulo_accept_local_resample", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_profile",
+           "mulo_accept_local_resample", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_resample_islands", "mulo_profile",
            "mulo_profile_read"]
 
 
@@ -78,6 +78,7 @@ def load_library():
                                      P, P, P, P, P, P, P, P, P]
     lib.mulo_resample_sequential.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P]
     lib.mulo_rejection_islands.argtypes = [P, I32, I32, I32, I32, P, P, P, P]
+    lib.mulo_resample_islands.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P, P, P]
     lib.mulo_profile.argtypes = [P, I32]
     lib.mulo_profile_read.argtypes = [P, C.POINTER(C.c_float), C.POINTER(I32)]
     for n in EXPORTS:
@@ -211,6 +212,16 @@ def mulo_rejection_islands(ctx, B, W, n0, L, mask, island, rank, counts):
     i32, u8 = torch.int32, torch.uint8
     _check(load_library().mulo_rejection_islands(ctx.handle, B, W, n0, L, _ptr(mask, u8), _ptr(island, i32), _ptr(rank, i32),
                                                  _ptr(counts, i32)), "mulo_rejection_islands")
+
+
+def mulo_resample_islands(ctx, kv, B, P, L, n_passes, max_islands, seed, rng_counter, prev_tokens, mask, rank, tokens,
+                          logits=None, overflow=None):
+    f32, i32, u8 = torch.float32, torch.int32, torch.uint8
+    kvs = KV(_ptr(kv[0], ctx.tdtype), _ptr(kv[1], ctx.tdtype))
+    _check(load_library().mulo_resample_islands(
+        ctx.handle, C.byref(kvs), B, P, L, n_passes, max_islands, C.c_uint64(seed), C.c_uint64(rng_counter),
+        _ptr(prev_tokens, i32), _ptr(mask, u8), _ptr(rank, i32), _ptr(tokens, i32), _ptr(logits, f32, True),
+        _ptr(overflow, i32, True)), "mulo_resample_islands")
 
 
 PROF_CLASSES = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention", "norm_embed",

@@ -38,6 +38,12 @@ struct AttnArgs {
     float scale_log2;  // log2(e) / sqrt(dh)
     int nsplit;        // > 1: the keys are dealt to nsplit workgroups per (sequence, head); one query tile only
     float* part;       // [nsplit, B, nh][dh + 2]: unnormalised output of the single query, running maximum, running sum
+    // scattered queries (island passes): query j of sequence b (L slots per sequence) sits at cache row
+    // pos_tab[b * L + j] in [P0, P0 + Lblk) (< 0: unused slot) and does not see rows P0 + t of its sequence with
+    // hide[b, t] set, its own excepted
+    const int32_t* pos_tab;
+    const uint8_t* hide;   // [B, Lblk]
+    int P0, Lblk;
 };
 constexpr int MAX_SPLIT = 16;
 
@@ -70,6 +76,8 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
         bh = bid / qtiles;
     }
     const int j0 = qt * BQ, hd = bh % a.nh, b = bh / a.nh;
+    const bool scattered = a.pos_tab != nullptr;
+    const int P = a.P;
     const int64_t hb = ((int64_t)a.layer * a.max_batch + b) * a.nh + hd;
     const bf16* kbase = a.kc + hb * a.max_seq * DH;
     const bf16* vbase = a.vc + hb * DH * a.max_seq;
@@ -77,7 +85,13 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
     // this lane's query (clamped for the ragged last tile; such lanes do not store)
     const int jq_raw = j0 + wave * 32 + l32;
     const int jq = jq_raw < a.L ? jq_raw : a.L - 1;
-    const int qpos = a.P + jq;
+    int qpos = P + jq;
+    bool active = true;
+    if (scattered) {   // the slot's own cache row; an unused slot computes on row P0 and stores zeros
+        const int row = a.pos_tab[(int64_t)b * a.L + jq];
+        active = row >= 0;
+        qpos = active ? row : a.P0;
+    }
     const int wave_jmin = j0 + wave * 32;
     int wave_jmax = wave_jmin + 31;
     wave_jmax = wave_jmax < a.L ? wave_jmax : a.L - 1;
@@ -92,7 +106,7 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
 
     int blk_jmax = j0 + BQ - 1;
     blk_jmax = blk_jmax < a.L ? blk_jmax : a.L - 1;
-    const int kmax_blk = a.P + blk_jmax;   // last key any query of this workgroup may see
+    const int kmax_blk = scattered ? a.P0 + a.Lblk - 1 : P + blk_jmax;   // last key any query of this workgroup may see
     const int n_tiles = kmax_blk / BKV + 1;
     // key split (single-token decoding): this workgroup covers tiles [t_begin, t_end) and leaves its
     // unnormalised partial result (output, running maximum, running sum) for k_attn_combine
@@ -165,7 +179,7 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
     for (int t = t_begin; t < t_end; ++t) {
         const int kv0 = t * BKV;
         const int t_next = t + 1 < t_end ? t + 1 : t;   // the last tile is fetched twice: no branch in the body
-        if (wave_live && kv0 <= a.P + wave_jmax) {
+        if (wave_live && (scattered || kv0 <= P + wave_jmax)) {
             gload(t_next);
             const bf16* k = sK + (t & 1) * BKV * KS;
             const bf16* v = sV + (t & 1) * DH * VS;
@@ -181,7 +195,7 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
                         *reinterpret_cast<const bf16x8*>(kr + kk * 16), qf[kk], s[kb], 0, 0, 0);
             }
             // accumulator r of block kb holds key kv0 + kb*32 + 16*(r/8) + 8*lh + r%8 for query l32
-            const bool need_mask = kv0 + BKV - 1 > a.P + wave_jmin;
+            const bool need_mask = scattered ? kv0 + BKV > a.P0 : kv0 + BKV - 1 > P + wave_jmin;
             float mx = -__builtin_huge_valf();
             if (need_mask) {
 #pragma unroll
@@ -192,6 +206,16 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
                         s[kb][r] = key <= qpos ? s[kb][r] : -__builtin_huge_valf();
                     }
             }
+            if (a.hide && kv0 + BKV > a.P0) {   // scattered queries: rows of positions that are not settled yet
+                const uint8_t* hd_row = a.hide + (int64_t)b * a.Lblk - a.P0;
+#pragma unroll
+                for (int kb = 0; kb < BKV / 32; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+                        if (key >= a.P0 && key < qpos && hd_row[key]) s[kb][r] = -__builtin_huge_valf();
+                    }
+            }
 #pragma unroll
             for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
@@ -199,7 +223,10 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             // running maximum in exponent units (scores times log2(e) / sqrt(dh)); the scale is positive
             const float m_new = fmaxf(m_run, mx * a.scale_log2);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            // a query that has seen no key yet (every row of its first tiles hidden) keeps -inf as its maximum:
+            // exponents are then taken against 0, which makes every term exp2(-inf) = 0 instead of NaN
+            const float m_safe = m_new == -__builtin_huge_valf() ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
             m_run = m_new;
             float ps = 0.f;
             bf16x8 pf[BKV / 16];
@@ -207,7 +234,7 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
             for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], a.scale_log2, -m_new));
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], a.scale_log2, -m_safe));
                     ps += p;
                     pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
                 }
@@ -256,7 +283,7 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
             for (int g4 = 0; g4 < 4; ++g4) {
                 bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[i][g4 * 4 + e] * inv);
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(active ? o[i][g4 * 4 + e] * inv : 0.f);
                 *reinterpret_cast<bf16x4*>(op + i * 32 + g4 * 8 + lh * 4) = w;
             }
     }
@@ -321,7 +348,7 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
         num += p[c] * wgt;
         den += p[DH + 1] * wgt;
     }
-    a.out[((int64_t)b * a.L) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(num / den);
+    a.out[((int64_t)b * a.L) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(den > 0.f ? num / den : 0.f);   // 0: unused slot
 }
 
 template <int DH, int BQ, int BKV, int NTH>
@@ -372,6 +399,22 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
     }
     if (head_dim == 128) run_attn<128>(a, st);
     else run_attn<64>(a, st);
+}
+
+void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
+                                     const int32_t* pos_tab, int cap, const uint8_t* hide, int P0, int Lblk,
+                                     int n_heads, int head_dim, int max_seq, int max_batch, int layer,
+                                     hipStream_t st) {
+    AttnArgs a{};
+    a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
+    a.B = B; a.L = cap; a.P = P0; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
+    a.scale_log2 = LOG2E / sqrtf((float)head_dim);
+    a.pos_tab = pos_tab; a.hide = hide; a.P0 = P0; a.Lblk = Lblk;
+    a.nsplit = 1;
+    a.part = nullptr;
+    // the slots of a sequence are the queries of one workgroup (128 per tile), which streams the sequence's rows once
+    if (head_dim == 128) run_attn_cfg<128, 128, BKV_SMALL, 256>(a, st);
+    else run_attn_cfg<64, 128, BKV_SMALL, 256>(a, st);
 }
 
 void launch_attention_f32(const float* q, const float* k_cache, const float* v_cache, float* out,

@@ -441,6 +441,62 @@ __global__ __launch_bounds__(TPB) void k_seq_draw(const float* __restrict__ logi
     cdf_draw(z, reinterpret_cast<const float4*>(z.zc), m, inv, true, word, V, *out, out, chunk, &s_retry);
 }
 
+// ---- island-parallel re-sampling (Sec. 3.4): one pass handles the rank-`pass` position of every island ----
+// One workgroup per sequence.  All threads write the pass's hidden set (marked positions whose rank is >= pass:
+// not re-drawn yet); the first wavefront then deals the positions of rank == pass to the sequence's `cap` slots in
+// raster order (ballot + prefix count, so the slot of a position does not depend on timing): its cache row, and
+// its input token = the current token of the position before it.  Unused slots get row -1.
+__global__ __launch_bounds__(TPB) void k_island_select(const int32_t* __restrict__ prev, const int32_t* __restrict__ tokens,
+                                                       const uint8_t* __restrict__ mask, const int32_t* __restrict__ rank,
+                                                       int32_t* __restrict__ pos_tab, int32_t* __restrict__ inp,
+                                                       uint8_t* __restrict__ hide, int32_t* __restrict__ overflow, int L,
+                                                       int P, int cap, int pass) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const uint8_t* mk = mask + (int64_t)b * L;
+    const int32_t* rk = rank + (int64_t)b * L;
+    for (int t = tid; t < L; t += TPB) hide[(int64_t)b * L + t] = mk[t] && rk[t] >= pass;
+    if (tid >= 64) return;
+    int cnt = 0;
+    for (int base = 0; base < L; base += 64) {
+        const int t = base + tid;
+        const bool sel = t < L && mk[t] && rk[t] == pass;
+        const unsigned long long bal = __ballot(sel);
+        const int slot = cnt + __popcll(bal & ((1ull << tid) - 1ull));
+        if (sel && slot < cap) {
+            pos_tab[b * cap + slot] = P + t;
+            inp[b * cap + slot] = t == 0 ? prev[b] : tokens[(int64_t)b * L + t - 1];
+        }
+        cnt += __popcll(bal);
+    }
+    for (int slot = cnt + tid; slot < cap; slot += 64) {
+        pos_tab[b * cap + slot] = -1;
+        inp[b * cap + slot] = 0;
+    }
+    if (tid == 0 && cnt > cap && overflow) atomicAdd(overflow, cnt - cap);   // the caller's bound was too small
+}
+
+// one workgroup per slot: tokens[sequence, u] ~ softmax(logits[slot, :]) for the position u the slot holds
+__global__ __launch_bounds__(TPB) void k_island_draw(const float* __restrict__ logits, const int32_t* __restrict__ pos_tab,
+                                                     int32_t* __restrict__ tokens, float* __restrict__ logits_out, int L,
+                                                     int V, int P, int cap, uint32_t key0, uint32_t key1, uint32_t ctr_lo,
+                                                     uint32_t ctr_hi24) {
+    __shared__ unsigned long long chunk[MAX_CHUNKS];
+    __shared__ int s_retry;
+    __shared__ float red[WAVES];
+    const int v = blockIdx.x, b = v / cap, row = pos_tab[v];
+    if (row < 0) return;   // uniform over the workgroup
+    const int u = row - P;
+    const Guided z{logits + (int64_t)v * V, nullptr, 1.f};
+    if (logits_out)
+        for (int c = threadIdx.x; c < V; c += TPB) logits_out[((int64_t)b * L + u) * V + c] = z.zc[c];
+    RowRegs<0> none;
+    float m, inv;
+    row_stats<0>(z, V, none, red, m, inv);
+    const uint32_t word = philox_word0((uint32_t)u, (uint32_t)b, ctr_lo, ctr_hi24 | (2u << 24), key0, key1);
+    int32_t* out = tokens + (int64_t)b * L + u;
+    cdf_draw(z, reinterpret_cast<const float4*>(z.zc), m, inv, true, word, V, *out, out, chunk, &s_retry);
+}
+
 // ---- rejection islands (Eq. 8): 8-connected components of the marked set, one workgroup per sequence ----
 // Labels live in LDS (one int per block position: 0 = unmarked, else 1 + a member's position).  Every round
 // a marked position takes the smallest label among itself and its 8 grid neighbours and then jumps to the
@@ -565,6 +621,20 @@ void launch_seq_draw(const float* logits, const uint8_t* mask, int32_t* tokens, 
     hipLaunchKernelGGL(k_seq_draw, dim3(B), dim3(TPB), 0, st, logits, mask, tokens, L, V, u,
                        (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), (uint32_t)(rng_counter & 0xFFFFFFFFu),
                        (uint32_t)((rng_counter >> 32) & 0xFFFFFFu));
+}
+
+void launch_island_select(const int32_t* prev, const int32_t* tokens, const uint8_t* mask, const int32_t* rank,
+                          int32_t* pos_tab, int32_t* inp, uint8_t* hide, int32_t* overflow, int B, int L, int P,
+                          int cap, int pass, hipStream_t st) {
+    hipLaunchKernelGGL(k_island_select, dim3(B), dim3(TPB), 0, st, prev, tokens, mask, rank, pos_tab, inp, hide,
+                       overflow, L, P, cap, pass);
+}
+
+void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* tokens, float* logits_out, int B,
+                        int L, int V, int P, int cap, uint64_t seed, uint64_t rng_counter, hipStream_t st) {
+    hipLaunchKernelGGL(k_island_draw, dim3(B * cap), dim3(TPB), 0, st, logits, pos_tab, tokens, logits_out, L, V, P,
+                       cap, (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
+                       (uint32_t)(rng_counter & 0xFFFFFFFFu), (uint32_t)((rng_counter >> 32) & 0xFFFFFFu));
 }
 
 void launch_accept(const DecideArgs& a, hipStream_t st) {

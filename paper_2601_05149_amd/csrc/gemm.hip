@@ -121,6 +121,15 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8s;
 // lane owns ONE token row (m = ... + l32) and, per block, the column runs [16 g + 8 lh, +8), g = 0, 1
 // (accumulators 8 g .. 8 g + 7).  The V projection keeps the operands in order: a lane owns one
 // output column and runs of 8 consecutive tokens, which are contiguous in the transposed V cache.
+// Where token row m of a projection lives: b, jj index the q buffer [B, nh, L, dh]; bc is its cache sequence and pos
+// its cache row (< 0: an unused slot of a scattered launch, nothing of it is written).
+struct TokPlace { int b, jj, bc, pos; };
+__device__ __forceinline__ TokPlace place(const RopeArgs& ra, int m) {
+    const int b = m / ra.L, jj = m % ra.L;
+    if (ra.pos_tab) return {b, jj, b, ra.pos_tab[m]};   // scattered queries: slot jj of sequence b (L slots each)
+    return {b, jj, b, ra.P + jj};
+}
+
 template <int EPI, int BN, int TM, int TN, int MB, int NB>
 __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB], int m0, int n0, int tile_n,
                                          int wm, int wn, int l32, int lh) {
@@ -186,10 +195,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB
                     const int mb = m0 + wm * TM + i * 32 + g2 * 16 + lh * 8;         // first of 8 tokens
                     if (n < g.N && mb < g.M) {
                         const int dh = g.ra.head_dim, hd = n / dh, cc = n % dh;
-                        const int b = mb / g.ra.L, jj = mb % g.ra.L;
-                        const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-                        bf16* dst = g.vc + (hb * dh + cc) * g.ra.max_seq + g.ra.P + jj;
-                        if (((g.ra.P | g.ra.L) & 7) == 0) {                          // aligned run inside one sequence
+                        if (!g.ra.pos_tab && ((g.ra.P | g.ra.L) & 7) == 0) {          // aligned run inside one sequence
+                            const int b = mb / g.ra.L, jj = mb % g.ra.L;
+                            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+                            bf16* dst = g.vc + (hb * dh + cc) * g.ra.max_seq + g.ra.P + jj;
                             bf16x8s o;
 #pragma unroll
                             for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
@@ -199,9 +208,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB
                             for (int e = 0; e < 8; ++e) {
                                 const int m = mb + e;
                                 if (m < g.M) {
-                                    const int b2 = m / g.ra.L, j2 = m % g.ra.L;
-                                    const int64_t hb2 = ((int64_t)g.ra.layer * g.ra.max_batch + b2) * g.ra.n_heads + hd;
-                                    g.vc[(hb2 * dh + cc) * g.ra.max_seq + g.ra.P + j2] = __float2bfloat16(v[e]);
+                                    const TokPlace pl = place(g.ra, m);
+                                    const int64_t hb2 = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                                    if (pl.pos >= 0) g.vc[(hb2 * dh + cc) * g.ra.max_seq + pl.pos] = __float2bfloat16(v[e]);
                                 }
                             }
                         }
@@ -246,23 +255,26 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB
                         } else {  // EPI_QK: rotary on the 4 adjacent pairs of the run, q -> [B, nh, L, dh], k -> cache row
                             const int n = n0 + wn * TN + cl, seg = n / g.d, c = n - seg * g.d;
                             const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
-                            const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
-                            const f32x4 cs = *reinterpret_cast<const f32x4*>(g.ra.cos + (int64_t)pos * (dh / 2) + (cc >> 1));
-                            const f32x4 sn = *reinterpret_cast<const f32x4*>(g.ra.sin + (int64_t)pos * (dh / 2) + (cc >> 1));
-                            bf16x8s o;
+                            const TokPlace pl = place(g.ra, m);
+                            if (pl.pos >= 0) {
+                                const int pos = pl.pos;
+                                const f32x4 cs = *reinterpret_cast<const f32x4*>(g.ra.cos + (int64_t)pos * (dh / 2) + (cc >> 1));
+                                const f32x4 sn = *reinterpret_cast<const f32x4*>(g.ra.sin + (int64_t)pos * (dh / 2) + (cc >> 1));
+                                bf16x8s o;
 #pragma unroll
-                            for (int pr = 0; pr < 4; ++pr) {
-                                o[2 * pr] = (__bf16)(v[2 * pr] * cs[pr] - v[2 * pr + 1] * sn[pr]);
-                                o[2 * pr + 1] = (__bf16)(v[2 * pr] * sn[pr] + v[2 * pr + 1] * cs[pr]);
+                                for (int pr = 0; pr < 4; ++pr) {
+                                    o[2 * pr] = (__bf16)(v[2 * pr] * cs[pr] - v[2 * pr + 1] * sn[pr]);
+                                    o[2 * pr + 1] = (__bf16)(v[2 * pr] * sn[pr] + v[2 * pr + 1] * cs[pr]);
+                                }
+                                bf16* dst;
+                                if (seg == 0) {
+                                    dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
+                                } else {
+                                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                                    dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
+                                }
+                                *reinterpret_cast<bf16x8s*>(dst) = o;
                             }
-                            bf16* dst;
-                            if (seg == 0) {
-                                dst = g.Cb + (((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc;
-                            } else {
-                                const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-                                dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
-                            }
-                            *reinterpret_cast<bf16x8s*>(dst) = o;
                         }
                     }
                 }
@@ -547,7 +559,7 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 }
 
 
-// ---- up to 32 tokens (single-token decoding of a few sequences): weight-streaming kernel ------------
+// ---- up to 64 tokens (single-token decoding of a few sequences, island passes): weight-streaming kernel ----
 // The work is reading every weight once, so nothing is staged: a workgroup owns 16 output columns (for
 // gate|up: 16 feed-forward columns = 16 gate rows + 16 up rows), its 8 wavefronts split K, and every lane
 // feeds v_mfma_f32_16x16x32_bf16 straight from global memory.  In that instruction's operand layout the four
@@ -555,14 +567,14 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 // of a wavefront reads 64 contiguous bytes of each of 16 rows: whole 64-byte sectors (with the 32-row
 // instruction only two lanes share a row, 32 of every 64 bytes fetched per request), and a matrix of N columns
 // gives N / 16 workgroups (256 for the 4096-column projections: one per CU).  The tokens are the instruction's
-// column dimension (columns m >= M are fed zeros), up to two groups of 16; the accumulators come out as
+// column dimension (columns m >= M are fed zeros), up to four groups of 16; the accumulators come out as
 // D[weight row 4 q + i][token l16], q = lane / 16: a lane owns 4 consecutive output columns of one token.  The
 // 8 partial sums are added in a fixed order through LDS and the epilogue runs on pairs of adjacent columns.
 typedef __attribute__((ext_vector_type(4))) float f32x4v;
 template <int EPI, int MT>
 __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;   // weight matrices (accumulator sets) per column
-    constexpr int U = 8;                            // 32-deep k-steps requested together
+    constexpr int U = MT <= 2 ? 8 : 4;              // 32-deep k-steps requested together
     __shared__ float part[8][NA * MT][4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, q = lane >> 4;
@@ -669,25 +681,28 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     } else if constexpr (EPI == EPI_QK) {
         const int seg = n / g.d, c = n - seg * g.d;
         const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
-        const int b = m / g.ra.L, jj = m % g.ra.L, pos = g.ra.P + jj;
+        const TokPlace pl = place(g.ra, m);
+        if (pl.pos < 0) return;
+        const int pos = pl.pos;
         const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
         bf16* dst;
         if (seg == 0) {
-            dst = g.Cb + (((int64_t)b * g.ra.n_heads + hd) * g.ra.L + jj) * dh + cc;
+            dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
         } else {
-            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
+            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
             dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
         }
         dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
         dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
     } else {   // EPI_V: transposed cache
         const int dh = g.ra.head_dim;
-        const int b = m / g.ra.L, jj = m % g.ra.L;
+        const TokPlace pl = place(g.ra, m);
+        if (pl.pos < 0) return;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int hd = (n + e) / dh, cc = (n + e) % dh;
-            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + b) * g.ra.n_heads + hd;
-            if (n + e < g.N) g.vc[(hb * dh + cc) * g.ra.max_seq + g.ra.P + jj] = __float2bfloat16(v0[e]);
+            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+            if (n + e < g.N) g.vc[(hb * dh + cc) * g.ra.max_seq + pl.pos] = __float2bfloat16(v0[e]);
         }
     }
 }
@@ -695,13 +710,16 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
 template <int EPI>
 void run_gemv(const GemmArgs& g, hipStream_t st) {
     const int cols = EPI == EPI_SWIGLU ? g.N / 2 : g.N;
-    if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1>), dim3((cols + 15) / 16), dim3(512), 0, st, g);
-    else hipLaunchKernelGGL((k_gemv_bf16<EPI, 2>), dim3((cols + 15) / 16), dim3(512), 0, st, g);
+    const dim3 grid((cols + 15) / 16);
+    if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1>), grid, dim3(512), 0, st, g);
+    else if (g.M <= 32) hipLaunchKernelGGL((k_gemv_bf16<EPI, 2>), grid, dim3(512), 0, st, g);
+    else if (g.M <= 48) hipLaunchKernelGGL((k_gemv_bf16<EPI, 3>), grid, dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((k_gemv_bf16<EPI, 4>), grid, dim3(512), 0, st, g);
 }
 
 template <int EPI>
 void dispatch(const GemmArgs& g, hipStream_t st) {
-    if (g.M <= 32 && (EPI != EPI_QK || g.d % 32 == 0)) {   // a handful of tokens: stream the weights
+    if (g.M <= 64 && (EPI != EPI_QK || g.d % 32 == 0)) {   // a handful of tokens: stream the weights
         run_gemv<EPI>(g, st);
         return;
     }

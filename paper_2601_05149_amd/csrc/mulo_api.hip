@@ -32,6 +32,8 @@ struct mulo_ctx {
     int32_t* tokens_hi;  // [maxM]
     int32_t* q_row;      // [maxL]
     float* attn_part;    // partial results of the key-split single-token attention
+    int32_t* isl_pos;    // [maxM] island-parallel re-sampling: cache row of every slot of a pass
+    uint8_t* isl_hide;   // [maxM] positions hidden from the queries of a pass
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
@@ -46,7 +48,7 @@ namespace {
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t off[14];
+    size_t off[16];
     size_t total;
 };
 
@@ -54,12 +56,13 @@ Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
     const size_t e = c.dtype == MULO_BF16 ? 2 : 4;
     const size_t tmpw = c.dtype == MULO_F32 ? (3 * d > 2 * f ? 3 * d : 2 * f) : 0;
-    const size_t sizes[14] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
+    const size_t sizes[16] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
                               M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
-                              c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0};
+                              c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0,
+                              M * 4, M};
     Layout l{};
     size_t o = 0;
-    for (int i = 0; i < 14; ++i) {
+    for (int i = 0; i < 16; ++i) {
         l.off[i] = o;
         o += align_up(sizes[i]);
     }
@@ -97,8 +100,17 @@ mulo_status check_forward_args(const mulo_ctx* ctx, const mulo_kv* kv, int B, in
     return MULO_OK;
 }
 
+// Scattered single-token queries (island-parallel re-sampling): the "block" is L slots per sequence, slot j of
+// sequence b sits at cache row pos_tab[b * L + j] (< 0: unused); rows P0 + t of a sequence with hide[b, t] set
+// are not attended to.
+struct Scatter {
+    const int32_t* pos_tab;
+    const uint8_t* hide;
+    int P0, Lblk;
+};
+
 void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_t* tok, const void* emb,
-                     float* logits) {
+                     float* logits, const Scatter* sc = nullptr) {
     const mulo_model_cfg& m = c->cfg;
     const int M = B * L, d = m.d_model, f = m.d_ffn, V = m.vocab, dt = m.dtype;
     const size_t e = c->esz;
@@ -106,6 +118,7 @@ void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     { PROF(MULO_PROF_NORM_EMBED); launch_embed(c->w.embed, dt, tok, emb, c->x, M, d, V, st); }
     for (int l = 0; l < m.n_layers; ++l) {
         RopeArgs ra{c->w.rope_cos, c->w.rope_sin, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l};
+        if (sc) ra.pos_tab = sc->pos_tab;
         const char* wq = (const char*)c->w.wq + (size_t)l * d * d * e;
         const char* wk = (const char*)c->w.wk + (size_t)l * d * d * e;
         const char* wv = (const char*)c->w.wv + (size_t)l * d * d * e;
@@ -119,8 +132,10 @@ void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
         if (dt == MULO_BF16) {
             { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
             { PROF(MULO_PROF_ATTENTION);
-              launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim, m.max_seq,
-                                    m.max_batch, l, st); }
+              if (sc) launch_attention_scattered_bf16(c->qbuf, kv->k, kv->v, c->att, B, sc->pos_tab, L, sc->hide, sc->P0,
+                                                      sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st);
+              else launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim,
+                                         m.max_seq, m.max_batch, l, st); }
             { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }
             { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
             { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, st); }
@@ -282,6 +297,8 @@ mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* 
     c->tokens_hi = (int32_t*)(b + l.off[11]);
     c->q_row = (int32_t*)(b + l.off[12]);
     c->attn_part = (float*)(b + l.off[13]);
+    c->isl_pos = (int32_t*)(b + l.off[14]);
+    c->isl_hide = (uint8_t*)(b + l.off[15]);
     *out = c;
     return MULO_OK;
 }
@@ -417,6 +434,31 @@ mulo_status mulo_resample_sequential(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int3
         if (logits)
             for (int b = 0; b < B; ++b)
                 launch_copy_rows(ctx->logits + (int64_t)b * V, logits + ((int64_t)b * L + u) * V, V, ctx->st);
+    }
+    return check_launch();
+}
+
+mulo_status mulo_resample_islands(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, int32_t L, int32_t n_passes,
+                                  int32_t max_islands, uint64_t seed, uint64_t rng_counter, const int32_t* prev_tokens,
+                                  const uint8_t* mask, const int32_t* rank, int32_t* tokens, float* logits,
+                                  int32_t* overflow) {
+    if (!ctx || !prev_tokens || !mask || !rank || !tokens) return MULO_ERR_NULL;
+    if (L < 1 || P < 0 || n_passes < 0 || max_islands < 1) return MULO_ERR_RANGE;
+    mulo_status s = check_forward_args(ctx, kv, B, 1, P + L - 1);
+    if (s != MULO_OK) return s;
+    if (ctx->cfg.dtype != MULO_BF16) return MULO_ERR_UNSUPPORTED;
+    const int64_t slots = (int64_t)B * max_islands;
+    if (slots > ctx->maxM || L > ctx->cfg.max_block) return MULO_ERR_SHAPE;   // the slots share the step's workspace
+    const int V = ctx->cfg.vocab;
+    mulo_ctx* c = ctx;
+    const Scatter sc{ctx->isl_pos, ctx->isl_hide, P, L};
+    for (int r = 0; r < n_passes; ++r) {
+        { PROF(MULO_PROF_OTHER);
+          launch_island_select(prev_tokens, tokens, mask, rank, ctx->isl_pos, ctx->inputs, ctx->isl_hide, overflow, B, L, P,
+                               max_islands, r, ctx->st); }
+        enqueue_forward(ctx, kv, B, max_islands, 0, ctx->inputs, nullptr, ctx->logits, &sc);
+        { PROF(MULO_PROF_MASK_SAMPLE);
+          launch_island_draw(ctx->logits, ctx->isl_pos, tokens, logits, B, L, V, P, max_islands, seed, rng_counter, ctx->st); }
     }
     return check_launch();
 }

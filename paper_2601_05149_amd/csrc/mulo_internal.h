@@ -45,6 +45,13 @@ void launch_islands(const uint8_t* mask, int32_t* island, int32_t* rank, int32_t
 void launch_seq_input(const int32_t* prev, const int32_t* tokens, int32_t* inp, int B, int L, int u, hipStream_t st);
 void launch_seq_draw(const float* logits, const uint8_t* mask, int32_t* tokens, int B, int L, int V, int u,
                      uint64_t seed, uint64_t rng_counter, hipStream_t st);
+// island-parallel re-sampling, pass `pass`: slots of the rank-`pass` positions (pos_tab, inputs), the hidden set
+// of the pass, and afterwards the draws of the slots from their logit rows
+void launch_island_select(const int32_t* prev, const int32_t* tokens, const uint8_t* mask, const int32_t* rank,
+                          int32_t* pos_tab, int32_t* inp, uint8_t* hide, int32_t* overflow, int B, int L, int P,
+                          int cap, int pass, hipStream_t st);
+void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* tokens, float* logits_out, int B,
+                        int L, int V, int P, int cap, uint64_t seed, uint64_t rng_counter, hipStream_t st);
 void launch_accept(const DecideArgs& a, hipStream_t st);       // init + softmax statistics + accept test
 void launch_mask_sample(const DecideArgs& a, hipStream_t st);  // Eq. 6-7 mask + residual draw
 void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t* inputs, int B,
@@ -55,6 +62,10 @@ struct RopeArgs {
     const float* cos;   // [max_seq, dh/2]
     const float* sin;
     int L, P, n_heads, head_dim, max_seq, max_batch, layer;
+    // Scattered single-token queries (island-parallel re-sampling): token m is slot m % L of sequence m / L and
+    // sits at cache row pos_tab[m] (< 0: an unused slot, nothing of it is written).  nullptr: token m is position
+    // m % L of sequence m / L, at cache row P + m % L.
+    const int32_t* pos_tab = nullptr;
 };
 // x[m, :] = embed[clamp(tok[m])]  (float32 residual stream); T = float or bf16 storage
 void launch_embed(const void* embed, int dtype, const int32_t* tok, const void* in_embeds, float* x,
@@ -76,6 +87,13 @@ size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim);   // p
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
                            int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,
                            int layer, hipStream_t st);
+// cap single-token queries per sequence at scattered cache rows: slot j of sequence b sits at row
+// pos_tab[b * cap + j] (< 0: unused slot, its output row is zeroed) and attends to rows <= its own except the rows
+// P0 + t of its sequence with hide[b, t] set (t < Lblk; its own row is never hidden).  Rows are in [P0, P0 + Lblk).
+void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
+                                     const int32_t* pos_tab, int cap, const uint8_t* hide, int P0, int Lblk,
+                                     int n_heads, int head_dim, int max_seq, int max_batch, int layer,
+                                     hipStream_t st);
 
 // float32 path (small configurations): plain tiled GEMM + separate elementwise kernels
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc,
