@@ -37,7 +37,7 @@ struct AttnArgs {
     int B, L, P, nh, max_seq, max_batch, layer;
     float scale_log2;  // log2(e) / sqrt(dh)
     int nsplit;        // > 1: the keys are dealt to nsplit workgroups per (sequence, head); one query tile only
-    float* part;       // [nsplit, B, nh][dh + 2]: unnormalised output of the single query, running maximum, running sum
+    float* part;       // [nsplit, B, nh, L][dh + 2]: unnormalised output of a query, running maximum, running sum (L <= 32)
     // scattered queries (island passes): query j of sequence b (L slots per sequence) sits at cache row
     // pos_tab[b * L + j] in [P0, P0 + Lblk) (< 0: unused slot) and does not see rows P0 + t of its sequence with
     // hide[b, t] set, its own excepted
@@ -46,6 +46,7 @@ struct AttnArgs {
     int P0, Lblk;
 };
 constexpr int MAX_SPLIT = 16;
+constexpr int SPLIT_QUERIES = 32;   // a key split serves at most this many queries per (sequence, head)
 
 template <int DH, int BQ, int BKV, int NTH>
 __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const AttnArgs a) {
@@ -76,7 +77,8 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
         bh = bid / qtiles;
     }
     const int j0 = qt * BQ, hd = bh % a.nh, b = bh / a.nh;
-    const bool scattered = a.pos_tab != nullptr;
+    // scattered queries run in the short-block configuration only; the long-block one keeps its registers
+    const bool scattered = BQ <= 128 && a.pos_tab != nullptr;
     const int P = a.P;
     const int64_t hb = ((int64_t)a.layer * a.max_batch + b) * a.nh + hd;
     const bf16* kbase = a.kc + hb * a.max_seq * DH;
@@ -108,15 +110,18 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
     blk_jmax = blk_jmax < a.L ? blk_jmax : a.L - 1;
     const int kmax_blk = scattered ? a.P0 + a.Lblk - 1 : P + blk_jmax;   // last key any query of this workgroup may see
     const int n_tiles = kmax_blk / BKV + 1;
-    // key split (single-token decoding): this workgroup covers tiles [t_begin, t_end) and leaves its
-    // unnormalised partial result (output, running maximum, running sum) for k_attn_combine
+    // key split (single-token decoding, island passes: at most 32 queries, one wavefront): this workgroup covers
+    // tiles [t_begin, t_end) and leaves its unnormalised partial results (output, running maximum, running sum)
+    // for k_attn_combine
     const int tiles_per = (n_tiles + a.nsplit - 1) / a.nsplit;
     const int t_begin = split * tiles_per, t_end = t_begin + tiles_per < n_tiles ? t_begin + tiles_per : n_tiles;
-    float* part = a.nsplit > 1 ? a.part + (((int64_t)split * a.B + b) * a.nh + hd) * (DH + 2) : nullptr;
+    float* part = a.nsplit > 1 ? a.part + (((int64_t)split * a.B + b) * a.nh + hd) * a.L * (DH + 2) : nullptr;
     if (t_begin >= t_end) {    // uniform over the workgroup, before any barrier: an empty share
         if (part) {
-            for (int c = tid; c < DH; c += NTH) part[c] = 0.f;
-            if (tid == 0) { part[DH] = -__builtin_huge_valf(); part[DH + 1] = 0.f; }
+            for (int c = tid; c < a.L * (DH + 2); c += NTH) {
+                const int e = c % (DH + 2);
+                part[c] = e == DH ? -__builtin_huge_valf() : 0.f;
+            }
         }
         return;
     }
@@ -206,14 +211,25 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
                         s[kb][r] = key <= qpos ? s[kb][r] : -__builtin_huge_valf();
                     }
             }
-            if (a.hide && kv0 + BKV > a.P0) {   // scattered queries: rows of positions that are not settled yet
-                const uint8_t* hd_row = a.hide + (int64_t)b * a.Lblk - a.P0;
+            if (BQ <= 128 && a.hide && kv0 + BKV > a.P0) {   // scattered queries: rows of positions that are not settled yet
+                // all flags of the tile are requested first (clamped into the block), then applied: a test per
+                // score would put every load behind the branch of the one before it
+                const uint8_t* hd_row = a.hide + (int64_t)b * a.Lblk;
+                uint8_t hidden[BKV / 32][16];
+#pragma unroll
+                for (int kb = 0; kb < BKV / 32; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int t = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7) - a.P0;
+                        t = t < 0 ? 0 : (t < a.Lblk ? t : a.Lblk - 1);
+                        hidden[kb][r] = hd_row[t];
+                    }
 #pragma unroll
                 for (int kb = 0; kb < BKV / 32; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
-                        if (key >= a.P0 && key < qpos && hd_row[key]) s[kb][r] = -__builtin_huge_valf();
+                        if (key >= a.P0 && key < qpos && hidden[kb][r]) s[kb][r] = -__builtin_huge_valf();
                     }
             }
 #pragma unroll
@@ -265,12 +281,13 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
 
     l_run += __shfl_xor(l_run, 32);
     if (part) {
-        if (wave == 0 && l32 == 0) {     // the single query of the tile
+        if (wave == 0 && jq_raw < a.L) {     // the tile's queries all belong to the first wavefront
+            float* pq = part + (int64_t)jq * (DH + 2);
 #pragma unroll
             for (int i = 0; i < NDB; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) part[i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3)] = o[i][r];
-            if (lh == 0) { part[DH] = m_run; part[DH + 1] = l_run; }
+                for (int r = 0; r < 16; ++r) pq[i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3)] = o[i][r];
+            if (lh == 0) { pq[DH] = m_run; pq[DH + 1] = l_run; }
         }
         return;
     }
@@ -338,17 +355,18 @@ __global__ __launch_bounds__(256) void k_attn_f32(const float* __restrict__ q, c
 // out[b, hd, :] = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s (maxima are in exponent units)
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
-    const int hd = blockIdx.x % a.nh, b = blockIdx.x / a.nh, c = threadIdx.x;
+    const int j = blockIdx.x % a.L, hd = (blockIdx.x / a.L) % a.nh, b = blockIdx.x / (a.L * a.nh), c = threadIdx.x;
+    auto share = [&](int s) { return a.part + ((((int64_t)s * a.B + b) * a.nh + hd) * a.L + j) * (DH + 2); };
     float M = -__builtin_huge_valf();
-    for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.B + b) * a.nh + hd) * (DH + 2) + DH]);
+    for (int s = 0; s < a.nsplit; ++s) M = fmaxf(M, share(s)[DH]);
     float num = 0.f, den = 0.f;
     for (int s = 0; s < a.nsplit; ++s) {
-        const float* p = a.part + (((int64_t)s * a.B + b) * a.nh + hd) * (DH + 2);
+        const float* p = share(s);
         const float wgt = __builtin_amdgcn_exp2f(p[DH] - M);
         num += p[c] * wgt;
         den += p[DH + 1] * wgt;
     }
-    a.out[((int64_t)b * a.L) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(den > 0.f ? num / den : 0.f);   // 0: unused slot
+    a.out[((int64_t)b * a.L + j) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(den > 0.f ? num / den : 0.f);
 }
 
 template <int DH, int BQ, int BKV, int NTH>
@@ -362,7 +380,7 @@ void run_attn_cfg(const AttnArgs& a, hipStream_t st) {
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B * a.nsplit), dim3(NTH), lds, st, a);
-    if (a.nsplit > 1) hipLaunchKernelGGL(k_attn_combine<DH>, dim3(a.B * a.nh), dim3(DH), 0, st, a);
+    if (a.nsplit > 1) hipLaunchKernelGGL(k_attn_combine<DH>, dim3(a.B * a.nh * a.L), dim3(DH), 0, st, a);
 }
 
 // Blocks of more than 128 queries: 256-query workgroups of 8 wavefronts over 128-key tiles (one per CU).  Shorter
@@ -377,7 +395,7 @@ void run_attn(const AttnArgs& a, hipStream_t st) {
 }  // namespace
 
 size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim) {
-    return (size_t)MAX_SPLIT * max_batch * n_heads * (head_dim + 2) * sizeof(float);
+    return (size_t)MAX_SPLIT * max_batch * n_heads * SPLIT_QUERIES * (head_dim + 2) * sizeof(float);
 }
 
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
@@ -401,18 +419,26 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
     else run_attn<64>(a, st);
 }
 
-void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
-                                     const int32_t* pos_tab, int cap, const uint8_t* hide, int P0, int Lblk,
-                                     int n_heads, int head_dim, int max_seq, int max_batch, int layer,
-                                     hipStream_t st) {
+void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                     float* scratch, int B, const int32_t* pos_tab, int cap, const uint8_t* hide,
+                                     int P0, int Lblk, int n_heads, int head_dim, int max_seq, int max_batch,
+                                     int layer, hipStream_t st) {
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = cap; a.P = P0; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
     a.pos_tab = pos_tab; a.hide = hide; a.P0 = P0; a.Lblk = Lblk;
+    // the slots of a sequence are the queries of one workgroup (128 per tile), which streams the sequence's rows
+    // once; with few (sequence, head) pairs and at most 32 slots the rows are dealt to several workgroups as well
     a.nsplit = 1;
-    a.part = nullptr;
-    // the slots of a sequence are the queries of one workgroup (128 per tile), which streams the sequence's rows once
+    a.part = scratch;
+    if (scratch && cap <= SPLIT_QUERIES) {
+        const int tiles = (P0 + Lblk - 1) / BKV_SMALL + 1;
+        int ns = 1024 / (B * n_heads);
+        ns = ns > MAX_SPLIT ? MAX_SPLIT : ns;
+        ns = ns > tiles ? tiles : ns;
+        a.nsplit = ns < 1 ? 1 : ns;
+    }
     if (head_dim == 128) run_attn_cfg<128, 128, BKV_SMALL, 256>(a, st);
     else run_attn_cfg<64, 128, BKV_SMALL, 256>(a, st);
 }

@@ -132,8 +132,8 @@ void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
         if (dt == MULO_BF16) {
             { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
             { PROF(MULO_PROF_ATTENTION);
-              if (sc) launch_attention_scattered_bf16(c->qbuf, kv->k, kv->v, c->att, B, sc->pos_tab, L, sc->hide, sc->P0,
-                                                      sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st);
+              if (sc) launch_attention_scattered_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, sc->pos_tab, L, sc->hide,
+                                                      sc->P0, sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st);
               else launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim,
                                          m.max_seq, m.max_batch, l, st); }
             { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }

@@ -90,10 +90,10 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
 // cap single-token queries per sequence at scattered cache rows: slot j of sequence b sits at row
 // pos_tab[b * cap + j] (< 0: unused slot, its output row is zeroed) and attends to rows <= its own except the rows
 // P0 + t of its sequence with hide[b, t] set (t < Lblk; its own row is never hidden).  Rows are in [P0, P0 + Lblk).
-void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, int B,
-                                     const int32_t* pos_tab, int cap, const uint8_t* hide, int P0, int Lblk,
-                                     int n_heads, int head_dim, int max_seq, int max_batch, int layer,
-                                     hipStream_t st);
+void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out,
+                                     float* scratch, int B, const int32_t* pos_tab, int cap, const uint8_t* hide,
+                                     int P0, int Lblk, int n_heads, int head_dim, int max_seq, int max_batch,
+                                     int layer, hipStream_t st);
 
 // float32 path (small configurations): plain tiled GEMM + separate elementwise kernels
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc,
