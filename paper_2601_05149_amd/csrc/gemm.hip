@@ -725,11 +725,19 @@ void dispatch(const GemmArgs& g, hipStream_t st) {
     }
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
-    const bool big = g.M >= 1024 && g.M % 256 == 0 && g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
-                      (int64_t)g.K * 256 * 2 < (1ll << 31) && (int64_t)g.M * g.K * 2 < (1ll << 31) &&
-                      (int64_t)(EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N) * g.K * 2 < (1ll << 31) &&
+    const bool whole_n = g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
+                         (int64_t)g.K * 256 * 2 < (1ll << 31) && (int64_t)g.M * g.K * 2 < (1ll << 31) &&
+                         (int64_t)(EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N) * g.K * 2 < (1ll << 31);
+    const bool big = whole_n && g.M >= 1024 && g.M % 256 == 0 &&
                      (int64_t)(g.M / 256) * (g.N / 256) * 4 >= 3 * (int64_t)cu_count();   // enough 256x256 tiles to fill the chip
-    if (big) {
+    // a few hundred tokens (any count: rows past M read as zeros through the descriptor and are not stored): the
+    // pipelined kernel on 128x256 tiles where their rounds are at least 80 % full (gate|up at 576 tokens: 430 tiles,
+    // +10 %; the lm-head's 320 tiles would leave the second round three quarters empty and lose 14 %)
+    const int64_t mid_tiles = (int64_t)((g.M + 127) / 128) * (g.N / 256), cus64 = cu_count();
+    const bool mid = !big && whole_n && g.M >= 256 && mid_tiles * 5 >= ((mid_tiles + cus64 - 1) / cus64) * cus64 * 4;
+    if (mid) {
+        run_gemm<128, 256, 4, 2, EPI, 64, true>(g, 0, g.N / 256, 1, st);
+    } else if (big) {
         // Whole rounds of 256x256 tiles, one tile per CU and round.  A last round that would leave more than
         // half of the CUs idle is cut off and run as 128x256 tiles (twice as many workgroups, half the work each).
         const int tiles_m = g.M / 256, tiles_n = g.N / 256, cus = cu_count();
