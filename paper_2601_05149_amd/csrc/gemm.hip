@@ -29,12 +29,14 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __hip_bfloat16 bf16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-enum { EPI_QK = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_V = 4 };
+enum { EPI_QK = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_V = 4,
+       EPI_QKV = 5 };   // q | k | v in one launch: weight-streaming kernel only
 
 struct GemmArgs {
     const bf16* A;        // [M, K]
     const bf16* W0;       // QK: wq | SWIGLU: w_gate | else: W [N, K]
     const bf16* W1;       // QK: wk | SWIGLU: w_up
+    const bf16* W2;       // QKV: wv
     int M, N, K;          // N: output columns of the fused problem (QK: 2d, SWIGLU: 2f)
     float* Cf;            // RESID: x [M, N] (+=) | LOGITS: logits [M, N]
     bf16* Cb;             // SWIGLU: h [M, N/2] | QK: q buffer
@@ -586,9 +588,9 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     const bf16* w[NA];
     {
         int r = n_blk + l16;
-        if constexpr (EPI == EPI_QK) {
-            const int seg = n_blk / g.d;                       // a block never straddles q | k (d % 16 == 0)
-            w[0] = (seg == 0 ? g.W0 : g.W1) + (int64_t)(r - seg * g.d) * g.K;
+        if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
+            const int seg = n_blk / g.d;                       // a block never straddles q | k | v (d % 16 == 0)
+            w[0] = (seg == 0 ? g.W0 : seg == 1 ? g.W1 : g.W2) + (int64_t)(r - seg * g.d) * g.K;
         } else if constexpr (EPI == EPI_SWIGLU) {
             const int f = g.N / 2;
             r = r < f ? r : f - 1;
@@ -678,7 +680,7 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
 #pragma unroll
         for (int e = 0; e < 2; ++e)
             if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
-    } else if constexpr (EPI == EPI_QK) {
+    } else if (EPI == EPI_QK || (EPI == EPI_QKV && n < 2 * g.d)) {
         const int seg = n / g.d, c = n - seg * g.d;
         const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
         const TokPlace pl = place(g.ra, m);
@@ -694,15 +696,16 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
         }
         dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
         dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
-    } else {   // EPI_V: transposed cache
+    } else {   // V: transposed cache
         const int dh = g.ra.head_dim;
+        const int nv = EPI == EPI_QKV ? n - 2 * g.d : n, nlim = EPI == EPI_QKV ? g.d : g.N;
         const TokPlace pl = place(g.ra, m);
         if (pl.pos < 0) return;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int hd = (n + e) / dh, cc = (n + e) % dh;
+            const int hd = (nv + e) / dh, cc = (nv + e) % dh;
             const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
-            if (n + e < g.N) g.vc[(hb * dh + cc) * g.ra.max_seq + pl.pos] = __float2bfloat16(v0[e]);
+            if (nv + e < nlim) g.vc[(hb * dh + cc) * g.ra.max_seq + pl.pos] = __float2bfloat16(v0[e]);
         }
     }
 }
@@ -800,6 +803,11 @@ void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const 
     GemmArgs g{};
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk;
     g.M = M; g.N = 2 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.d = d; g.ra = ra;
+    if (M <= 64 && d % 32 == 0) {   // a handful of tokens: q | k | v stream through one launch
+        g.W2 = (const bf16*)wv; g.vc = (bf16*)v_cache; g.N = 3 * d;
+        run_gemv<EPI_QKV>(g, st);
+        return;
+    }
     dispatch<EPI_QK>(g, st);
     GemmArgs v{};
     v.A = (const bf16*)xh; v.W0 = (const bf16*)wv; v.M = M; v.N = d; v.K = d; v.vc = (bf16*)v_cache; v.ra = ra;
