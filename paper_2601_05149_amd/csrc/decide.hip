@@ -229,12 +229,6 @@ __global__ void k_shift_inputs(const int32_t* __restrict__ prev, const int32_t* 
 }
 
 // ---- Step 4: softmax statistics + accept test, one workgroup per position ---
-__global__ void k_decide_init(int32_t* t0, int32_t* stats, int B, int L) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B) t0[i] = L;
-    if (i < 4 * B) stats[i] = 0;
-}
-
 __device__ __forceinline__ int clamp_tok(int t, int V) { return t < 0 ? 0 : (t >= V ? V - 1 : t); }
 
 template <int NV4>
@@ -279,9 +273,79 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
         a.accept[row] = ok ? 1 : 0;
         a.rowmax[row] = m;
         a.rowinv[row] = inv;
-        atomicAdd(&a.stats[b * 4 + (ok ? 0 : 1)], 1);
-        if (!ok) atomicMin(&a.t0[b], t);
-        if (fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, tau_rule ? a.tau : qt)) atomicAdd(&a.stats[b * 4 + 3], 1);
+        // near-tie flag, parked in the mask array until k_decide_finish has counted it (per-row atomics on the
+        // few counters of a sequence cost a quarter of this kernel's time)
+        a.mask[row] = fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, tau_rule ? a.tau : qt) ? 1 : 0;
+    }
+}
+
+// ---- Step 5 (Eq. 6-7) + the step's counters, one workgroup per sequence ----
+// From the accept flags of the block (staged in LDS): t0 = first rejected position, the counts of accepted /
+// rejected positions and near ties, then R_X: position t is marked when it is at or after t0 and within Chebyshev
+// distance rho of some rejected position of the block (rho < 0: the raster rule, everything from t0 on).  Writes
+// mask, t0 and stats = (accepted, rejected, marked, near ties); no atomics on global memory anywhere.
+__global__ __launch_bounds__(TPB) void k_decide_finish(const DecideArgs a) {
+    extern __shared__ uint8_t acc_s[];   // [L]
+    __shared__ int red[WAVES][4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint8_t* acc_g = a.accept + (int64_t)b * a.L;
+    uint8_t* mask_g = a.mask + (int64_t)b * a.L;
+    int n_acc = 0, n_near = 0, tmin = a.L;
+    for (int t = tid; t < a.L; t += TPB) {
+        const uint8_t ok = acc_g[t];
+        acc_s[t] = ok;
+        n_acc += ok;
+        n_near += mask_g[t];
+        if (!ok && t < tmin) tmin = t;
+    }
+    auto reduce3 = [&](int& x, int& y, int& z_min, int& w) {   // sums of x, y, w and the minimum of z_min over the workgroup
+        for (int o = 32; o > 0; o >>= 1) {
+            x += __shfl_xor(x, o);
+            y += __shfl_xor(y, o);
+            w += __shfl_xor(w, o);
+            const int other = __shfl_xor(z_min, o);
+            z_min = other < z_min ? other : z_min;
+        }
+        __syncthreads();
+        if (lane == 0) { red[wv][0] = x; red[wv][1] = y; red[wv][2] = z_min; red[wv][3] = w; }
+        __syncthreads();
+        x = y = w = 0;
+        z_min = a.L;
+        for (int i = 0; i < WAVES; ++i) {
+            x += red[i][0]; y += red[i][1]; w += red[i][3];
+            z_min = red[i][2] < z_min ? red[i][2] : z_min;
+        }
+    };
+    int zero = 0;
+    reduce3(n_acc, n_near, tmin, zero);   // the barriers inside also publish acc_s and retire the reads of mask_g
+    const int t0 = tmin;
+    int n_marked = 0;
+    for (int t = tid; t < a.L; t += TPB) {
+        int marked = 0;
+        if (t >= t0) {
+            if (a.rho < 0) {
+                marked = 1;
+            } else {
+                // the window, cut to the rows of the block (whole rows of the grid) and to the grid's columns
+                const int g = a.n0 + t, gi = g / a.W, gj = g % a.W, r0 = a.n0 / a.W, r1 = (a.n0 + a.L - 1) / a.W;
+                const int i_lo = gi - a.rho > r0 ? gi - a.rho : r0, i_hi = gi + a.rho < r1 ? gi + a.rho : r1;
+                const int j_lo = gj - a.rho > 0 ? gj - a.rho : 0, j_hi = gj + a.rho < a.W - 1 ? gj + a.rho : a.W - 1;
+                for (int ii = i_lo; ii <= i_hi && !marked; ++ii)
+                    for (int jj = j_lo; jj <= j_hi; ++jj)
+                        if (acc_s[ii * a.W + jj - a.n0] == 0) { marked = 1; break; }
+            }
+        }
+        mask_g[t] = (uint8_t)marked;
+        n_marked += marked;
+    }
+    int d0 = 0, d1 = a.L;
+    reduce3(n_marked, d0, d1, zero);
+    if (tid == 0) {
+        a.t0[b] = t0;
+        a.stats[b * 4 + 0] = n_acc;
+        a.stats[b * 4 + 1] = a.L - n_acc;
+        a.stats[b * 4 + 2] = n_marked;
+        a.stats[b * 4 + 3] = n_near;
     }
 }
 
@@ -377,33 +441,13 @@ __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
     const int64_t row = blockIdx.x;
     const int b = row / a.L, t = row % a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 
-    // R_X membership of this position (Eq. 6-7): at or after t0 and within
-    // Chebyshev distance rho of some rejected position of the block.
-    int marked = 0;
-    const int t0 = a.t0[b];
-    if (t >= t0) {
-        if (a.rho < 0) {
-            marked = 1;
-        } else {
-            const int g = a.n0 + t, gi = g / a.W, gj = g % a.W, side = 2 * a.rho + 1;
-            for (int c = tid; c < side * side; c += TPB) {
-                const int ii = gi + c / side - a.rho, jj = gj + c % side - a.rho;
-                if (ii >= 0 && ii < a.H && jj >= 0 && jj < a.W) {
-                    const int tt = ii * a.W + jj - a.n0;
-                    if (tt >= 0 && tt < a.L && a.accept[(int64_t)b * a.L + tt] == 0) marked = 1;
-                }
-            }
-        }
-    }
-    marked = __syncthreads_or(marked);
+    // R_X membership of this position (Eq. 6-7) was decided by k_decide_finish
+    const int marked = a.mask[row];
     const int draft = clamp_tok(a.draft_tokens[row], a.V);
-    if (tid == 0) {
-        a.mask[row] = marked ? 1 : 0;
-        if (marked) atomicAdd(&a.stats[b * 4 + 2], 1);
-        else a.tokens_out[row] = draft;
+    if (!marked) {   // uniform over the workgroup
+        if (tid == 0) a.tokens_out[row] = draft;
+        return;
     }
-    if (!marked) return;
-
     // Residual draw through the integer CDF
     const int V = a.V;
     const Guided z{a.logits + row * V, a.logits_u ? a.logits_u + row * V : nullptr, a.cfg_scale};
@@ -637,9 +681,17 @@ void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* to
                        (uint32_t)(rng_counter & 0xFFFFFFFFu), (uint32_t)((rng_counter >> 32) & 0xFFFFFFu));
 }
 
+void launch_decide_finish(const DecideArgs& a, hipStream_t st) {   // a.L <= 131072 (the caller checks): flags in LDS
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_decide_finish),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_decide_finish, dim3(a.B), dim3(TPB), (size_t)a.L, st, a);
+}
+
 void launch_accept(const DecideArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(k_decide_init, dim3((4 * a.B + 255) / 256), dim3(256), 0, st, a.t0, a.stats, a.B,
-                       a.L);
     if (a.V <= 1024) accept_inst<1>(a, st);
     else if (a.V <= 2048) accept_inst<2>(a, st);
     else if (a.V <= 4096) accept_inst<4>(a, st);

@@ -181,6 +181,7 @@ void enqueue_upsample(mulo_ctx* c, int B, int h, int w, int r, const float* draf
 
 void enqueue_decide(mulo_ctx* c, const DecideArgs& a) {
     { PROF(MULO_PROF_ACCEPT); launch_accept(a, c->st); }
+    { PROF(MULO_PROF_OTHER); launch_decide_finish(a, c->st); }
     { PROF(MULO_PROF_MASK_SAMPLE); launch_mask_sample(a, c->st); }
 }
 
@@ -249,6 +250,7 @@ mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mul
         return MULO_ERR_RANGE;
     if ((int64_t)p->radius * p->expand > 4096) return MULO_ERR_RANGE;
     if ((p->cfg_scale > 0.f ? 2 * (int64_t)B : (int64_t)B) > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
+    if (p->L > 131072) return MULO_ERR_UNSUPPORTED;   // the accept flags of a block are staged in LDS
     if (p->L % p->W || p->n0 % p->W || (int64_t)p->n0 + p->L > (int64_t)p->H * p->W) return MULO_ERR_SHAPE;
     if (p->pool_k > 1 && !p->nbr) return MULO_ERR_NULL;
     if (p->pool_k > c->vocab) return MULO_ERR_RANGE;

@@ -52,8 +52,9 @@ void launch_island_select(const int32_t* prev, const int32_t* tokens, const uint
                           int cap, int pass, hipStream_t st);
 void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* tokens, float* logits_out, int B,
                         int L, int V, int P, int cap, uint64_t seed, uint64_t rng_counter, hipStream_t st);
-void launch_accept(const DecideArgs& a, hipStream_t st);       // init + softmax statistics + accept test
-void launch_mask_sample(const DecideArgs& a, hipStream_t st);  // Eq. 6-7 mask + residual draw
+void launch_accept(const DecideArgs& a, hipStream_t st);         // softmax statistics + accept test
+void launch_decide_finish(const DecideArgs& a, hipStream_t st);  // t0, Eq. 6-7 mask, the step's counters
+void launch_mask_sample(const DecideArgs& a, hipStream_t st);    // residual draw of the marked positions
 void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t* inputs, int B,
                          int L, hipStream_t st);
 
