@@ -298,7 +298,7 @@ __global__ __launch_bounds__(TPB) void k_decide_finish(const DecideArgs a) {
         n_near += mask_g[t];
         if (!ok && t < tmin) tmin = t;
     }
-    auto reduce3 = [&](int& x, int& y, int& z_min, int& w) {   // sums of x, y, w and the minimum of z_min over the workgroup
+    auto reduce_counts = [&](int& x, int& y, int& z_min, int& w) {   // sums of x, y, w and the minimum of z_min over the workgroup
         for (int o = 32; o > 0; o >>= 1) {
             x += __shfl_xor(x, o);
             y += __shfl_xor(y, o);
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(TPB) void k_decide_finish(const DecideArgs a) {
         }
     };
     int zero = 0;
-    reduce3(n_acc, n_near, tmin, zero);   // the barriers inside also publish acc_s and retire the reads of mask_g
+    reduce_counts(n_acc, n_near, tmin, zero);   // the barriers inside also publish acc_s and retire the reads of mask_g
     const int t0 = tmin;
     int n_marked = 0;
     for (int t = tid; t < a.L; t += TPB) {
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(TPB) void k_decide_finish(const DecideArgs a) {
         n_marked += marked;
     }
     int d0 = 0, d1 = a.L;
-    reduce3(n_marked, d0, d1, zero);
+    reduce_counts(n_marked, d0, d1, zero);
     if (tid == 0) {
         a.t0[b] = t0;
         a.stats[b * 4 + 0] = n_acc;
