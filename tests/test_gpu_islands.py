@@ -103,8 +103,11 @@ def _compare(m, w, r, mask, seed, ctr, round_bf16, logit_tol):
 SMALL = dict(n_layers=2, d_model=256, n_heads=4, head_dim=64, d_ffn=512, vocab=2048, dtype="bf16", rms_eps=1e-5)
 
 
-def test_islands_small_bf16_several_islands_vs_oracle():
-    m = SMALL
+WIDE_HEADS = dict(n_layers=2, d_model=256, n_heads=2, head_dim=128, d_ffn=512, vocab=2048, dtype="bf16", rms_eps=1e-5)
+
+
+@pytest.mark.parametrize("m", [SMALL, WIDE_HEADS], ids=["dh64", "dh128"])
+def test_islands_small_bf16_several_islands_vs_oracle(m):
     w = G.make_weights(m, seed=0, threads=4)
     B, Pn, H, W = 3, 9, 8, 8
     L = H * W
