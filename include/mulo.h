@@ -135,7 +135,8 @@ typedef struct {
 /* Static description of a status code; never NULL. */
 MULO_API const char *mulo_status_string(mulo_status s);
 
-/* Pure host-side checks (no GPU needed), also run by the entry points below. */
+/* Pure host-side checks (no GPU needed), also run by the entry points below.  Among them: a block of more than
+ * 131072 positions is MULO_ERR_UNSUPPORTED (the accept flags of a block are staged in the LDS of one workgroup). */
 MULO_API mulo_status mulo_check_model_cfg(const mulo_model_cfg *cfg);
 MULO_API mulo_status mulo_check_step_params(const mulo_model_cfg *cfg, int32_t B, const mulo_step_params *p);
 

@@ -78,6 +78,11 @@ def test_step_param_checks(lib):
     assert ok(**{**base, "accept_mode": 2}) == 3
     assert ok(**{**base, "B": 5}) == 2
     assert lib.mulo_check_step_params(C.byref(cfg), 4, None) == 1
+    # a block whose accept flags do not fit the LDS of the per-sequence kernel
+    long_cfg = mulo.make_cfg(c["model"], 1, 1 << 19, 1 << 18)
+    huge = dict(base, H=512, W=512, n0=0, L=1 << 18)
+    assert lib.mulo_check_step_params(C.byref(long_cfg), 1, C.byref(BD.StepParams(**huge))) == 6
+    assert lib.mulo_check_step_params(C.byref(long_cfg), 1, C.byref(BD.StepParams(**dict(huge, L=1 << 17)))) == 0
 
 
 def test_create_rejects_bad_arguments_without_a_gpu_call(lib):
