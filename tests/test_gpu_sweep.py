@@ -3,12 +3,13 @@ blocks of 256 / 512 / 1024 tokens, draft-logit noise sigma in {0.5, 1, 2}) at it
 full launch shapes through mulo_verify_step.
 
 The oracle cannot recompute a 16 x 1024-token 7B forward (hours of float64), so
-the forward is checked by what holds at any size: a sequence of the batched
-launch equals the same sequence launched alone (sequences are independent), whose
-per-sequence shapes (P = 3200 .. 3968, L = 256 .. 1024) the single-sequence
-oracle comparisons of test_gpu_forward.py cover.  The decision stage is compared
-with the oracle on the device's own logits: the whole batch at L = 256 for every
-sigma, the first two sequences at L = 512 and 1024."""
+the forward is checked on a sample and by what holds at any size: the oracle
+recomputes sequence 0 of the L = 256 launch, and a sequence of every batched
+launch equals the same sequence launched alone (sequences are independent; the
+L = 1024 per-sequence shape is the one test_gpu_forward.py compares in full).
+The decision stage is compared with the oracle on the device's own logits: the
+whole batch at L = 256 for every sigma, the first two sequences at L = 512 and
+1024."""
 import numpy as np
 import pytest
 import torch
@@ -16,8 +17,8 @@ import torch
 import paper_2601_05149_amd as mulo
 from oracle import step as ST
 from oracle import upsample as UP
-from tests.gpu_util import DEV, compare_decisions, decide_buffers, make_ctx, say, to_np
-from tests.test_gpu_forward import weights_7b
+from tests.gpu_util import DEV, check_bf16_logits, compare_decisions, decide_buffers, make_ctx, say, to_np
+from tests.test_gpu_forward import pair, weights_7b
 from workloads import configs as WC
 
 pytestmark = pytest.mark.gpu
@@ -55,7 +56,7 @@ def test_sweep_full_launches_decisions_and_sequence_independence():
     c0 = WC.get("cfg5_L1024")
     m, B, S = c0["model"], c0["B"], c0["max_seq"]
     V = m["vocab"]
-    ctx, _, _ = make_ctx(m, w, B, S, 1024)
+    ctx, cos, sin = make_ctx(m, w, B, S, 1024)
     ctx1, _, _ = make_ctx(m, w, 1, S, 1024)
     kv = mulo.alloc_kv(ctx, DEV)
     gen = torch.Generator(device=DEV).manual_seed(5)
@@ -98,6 +99,21 @@ def test_sweep_full_launches_decisions_and_sequence_independence():
             assert np.array_equal(got["tokens_out"][keep], thi.cpu().numpy()[keep])
             assert np.array_equal(got["stats"][:, 0] + got["stats"][:, 1], np.full(B, L))
             assert np.array_equal(got["stats"][:, 2], got["mask"].sum(1))
+            if sigma == 1.0 and L == 256:
+                # the oracle recomputes the first sequence of the batched launch (256 tokens against 3968 cache rows,
+                # which are copied from the device: rounded and exact decoder, the bf16 bar of the forward tests)
+                say("  oracle forward of sequence 0 (rounded + exact) ...")
+                nl, nh, dh = m["n_layers"], m["n_heads"], m["head_dim"]
+                dr, du = pair(m, w, cos, sin, 1, S)
+                k0 = kv[0][:, 0, :, :P].float().cpu()                       # [nl, nh, P, dh]
+                v0 = kv[1][:, 0, :, :, :P].float().cpu().permute(0, 1, 3, 2)  # [nl, nh, dh, P] -> [nl, nh, P, dh]
+                for d_ in (dr, du):
+                    d_.k[:, 0, :P] = k0.permute(0, 2, 1, 3).to(d_.k.dtype)
+                    d_.v[:, 0, :P] = v0.permute(0, 2, 1, 3).to(d_.v.dtype)
+                inp0 = torch.cat([prev[:1].reshape(1, 1), thi[:1, :L - 1]], dim=1).cpu().numpy()
+                check_bf16_logits("sweep L=256 b=0", logits[:1].cpu().numpy(), dr.forward(inp0, P).numpy(),
+                                  du.forward(inp0, P).numpy())
+                del dr, du, k0, v0
             if sigma == 1.0:
                 # the last sequence alone (its own context, cache and workspace) reproduces its rows of the batch
                 b = B - 1
