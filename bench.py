@@ -59,6 +59,58 @@ def cpu_baseline(c, w, cos, sin, seed):
                           Ls, c["r"], P, c["name"], nl, dt_s)}
 
 
+def resample_bench(mulo, ctx, kv, c, B, L, P, V, rate, seed, gen):
+    """Re-sampling of the marked positions of one block (Alg. 1 Step 6; Sec. 3.4): a synthetic verification rejects
+    each position with probability `rate`, R_X is the radius-1 neighbourhood of the rejections from the first one
+    on (Eq. 6-7), and both re-samplers run on it.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    dev = "cuda:0"
+    W = c["W"]
+    rows = L // W
+    rng = np.random.default_rng(seed)
+    rej = rng.random((B, rows, W)) < rate
+    rej[:, rows // 2, W // 2] = True                       # at least one rejection per sequence
+    mask = np.zeros_like(rej)
+    for b, i, j in zip(*np.nonzero(rej)):
+        mask[b, max(i - 1, 0):i + 2, max(j - 1, 0):j + 2] = True
+    mask = mask.reshape(B, L)
+    t0s = [int(np.flatnonzero(rej[b].reshape(-1))[0]) for b in range(B)]
+    for b in range(B):
+        mask[b, :t0s[b]] = False
+    mask_d = torch.tensor(mask.astype(np.uint8), device=dev)
+    island = torch.empty(B, L, dtype=torch.int32, device=dev)
+    rank = torch.empty_like(island)
+    counts = torch.empty(B, 2, dtype=torch.int32, device=dev)
+    mulo.mulo_rejection_islands(ctx, B, W, c["T"] - L, L, mask_d, island, rank, counts)
+    cn = counts.cpu().numpy()
+    cap, passes = int(cn[:, 0].max()), int(cn[:, 1].max())
+    tokens = torch.randint(0, V, (B, L), generator=gen, device=dev, dtype=torch.int32)
+    prev = torch.zeros(B, dtype=torch.int32, device=dev)
+    u_start = min(t0s)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t)
+
+    ms_isl = timed(lambda: mulo.mulo_resample_islands(ctx, kv, B, P, L, passes, cap, seed, 0, prev, mask_d, rank, tokens))
+    ms_seq = timed(lambda: mulo.mulo_resample_sequential(ctx, kv, B, P, L, u_start, seed, 0, prev, mask_d, tokens))
+    tok1 = torch.randint(0, V, (B, 1), generator=gen, device=dev, dtype=torch.int32)
+    z1 = torch.empty(B, 1, V, device=dev)
+    ms_tok = timed(lambda: [mulo.mulo_verify_forward(ctx, kv, B, 1, P + L - 1, tok1, None, z1) for _ in range(20)]) / 20
+    print(json.dumps({
+        "metric": "re-sampling of one verified block (1 GPU)", "unit": "ms", "higher_is_better": False, "data": "synthetic",
+        "config": {"workload": "%s: last block, B=%d L=%d P=%d, rejection rate %g, radius 1" % (c["name"], B, L, P, rate)},
+        "marked_positions": int(mask.sum()), "islands_per_sequence": cn[:, 0].tolist(), "largest_island": cn[:, 1].tolist(),
+        "island_passes": passes, "slots_per_pass": B * cap, "sequential_steps": L - u_start,
+        "ms_islands": round(ms_isl, 2), "ms_sequential": round(ms_seq, 2), "ms_single_token_step": round(ms_tok, 3),
+        "ms_per_island_pass": round(ms_isl / max(passes, 1), 3)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +122,10 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--profile-all", action="store_true",
                     help="bracket every kernel class (adds ~3 %% to the step); default: only the roofline kernel")
+    ap.add_argument("--resample", type=float, default=None, metavar="RATE",
+                    help="instead of the verify step: time the re-sampling of the workload's last block after a "
+                         "synthetic verification with this fraction of rejected positions (radius 1) - "
+                         "mulo_resample_islands against mulo_resample_sequential, and one single-token target step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB read + 1 GiB write element-wise kernel (scale for HBM byte counters)")
     a = ap.parse_args()
@@ -118,6 +174,10 @@ def main():
     gen = torch.Generator(device=dev).manual_seed(seed)
     kv[0][:, :, :, :P].normal_(generator=gen)
     kv[1][:, :, :, :, :P].normal_(generator=gen)
+
+    if a.resample is not None:
+        resample_bench(mulo, ctx, kv, c, B, L, P, V, a.resample, seed, gen)
+        return
 
     # draft recipe ("target-like logits + N(0, sigma)"): provisional uniform draft -> un-timed forward ->
     # draft logits = target logits of the top-left child + sigma * noise -> draft tokens ~ softmax(draft logits)
