@@ -203,7 +203,8 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.status == 3
 
 
-@pytest.mark.parametrize("name,B,L,radius", [("cfg4", 4, 1024, 2), ("cfg5_L256", 16, 256, 1)])
+@pytest.mark.parametrize("name,B,L,radius", [("cfg4", 4, 1024, 2), ("cfg5_L256", 16, 256, 1), ("cfg5_L512", 16, 512, 1),
+                                                ("cfg5_L1024", 16, 1024, 1)])
 def test_decide_full_size(name, B, L, radius):
     """Decision stage at the full shape of the 7B-class workloads (V = 16384,
     64x64 grid, last block), in the launch configuration the benchmark times."""
