@@ -24,6 +24,13 @@
  *   - All work is enqueued on the HIP stream given to mulo_create; nothing
  *     synchronises with the host.  Outputs are valid once the caller has
  *     synchronised that stream.  A context is not thread-safe.
+ *   - The compute entry points enqueue kernels only (no allocation, no memset
+ *     or copy node, no host synchronisation after mulo_create), so a call may be
+ *     recorded into a HIP graph by stream capture on that stream and replayed,
+ *     once an ordinary call of the same entry point has run (the first launch of
+ *     a kernel configures it).  Host structs are read at record time: a replay
+ *     repeats the recorded seed and rng_counter.  Profiling (mulo_profile)
+ *     must be off while recording.
  *   - Every argument is checked before anything is launched; on an error
  *     nothing has been written.  No entry point prints, throws or aborts.
  *   - Token grids are raster order: position u of an H x W grid sits at row
