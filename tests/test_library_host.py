@@ -94,3 +94,14 @@ def test_create_rejects_bad_arguments_without_a_gpu_call(lib):
     assert lib.mulo_create(C.byref(cfg), C.byref(w), None, C.byref(out)) == 1
     assert not out.value
     lib.mulo_destroy(None)                           # allowed
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: the benchmark says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300, cwd=root)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr + r.stdout and '"metric"' not in r.stdout
