@@ -30,8 +30,8 @@ def log(msg):
 
 
 def cpu_baseline(c, w, cos, sin, seed):
-    """The oracle as it stands on a bounded sample: batch element 0, one grid row
-    (W tokens) as the draft block, against the full-length seeded cache."""
+    """The oracle as it stands on a bounded sample: batch element 0, two low-resolution rows (2 r grid rows)
+    as the draft block, against the full-length seeded cache."""
     import numpy as np
     import torch
 
@@ -40,23 +40,24 @@ def cpu_baseline(c, w, cos, sin, seed):
     from workloads import generators as G
     m = c["model"]
     nl, nh, dh, V = m["n_layers"], m["n_heads"], m["head_dim"], m["vocab"]
-    Ls = c["W"] * c["r"]                  # r grid rows: the smallest whole-row block the up-sampler can feed
+    h_blk = min(2, c["L"] // c["W"] // c["r"])   # low-resolution rows behind the sample block
+    Ls = h_blk * c["W"] * c["r"]
     P = c["max_seq"] - c["L"]
     dec = OD.DecoderOracle(m, w, cos, sin, 1, P + Ls, round_bf16=(m["dtype"] == "bf16"))
     dec.k[:, 0, :P] = G.random_kv((nl, nh, P, dh), seed, tag=0).permute(0, 2, 1, 3).to(dec.k.dtype)
     dec.v[:, 0, :P] = G.random_kv((nl, nh, P, dh), seed, tag=1).permute(0, 2, 1, 3).to(dec.v.dtype)
-    n_lo = Ls // (c["r"] * c["r"])
+    n_lo = h_blk * c["w"]
     dl = G.normal_logits((1, n_lo, V), 2.0, seed, tag=7)
     dt = G.sample_categorical(dl, seed, tag=7)
     threads = torch.get_num_threads()
     t0 = time.perf_counter()
-    OS.verify_step(dec, P, dl, dt, np.zeros(1, np.int32), h_blk=1, w=c["w"], r=c["r"], W=c["W"],
+    OS.verify_step(dec, P, dl, dt, np.zeros(1, np.int32), h_blk=h_blk, w=c["w"], r=c["r"], W=c["W"],
                    n0=c["T"] - c["L"], radius=c["radius"], expand=c["expand"], seed=seed, rng_counter=0)
     dt_s = time.perf_counter() - t0
     return {"value": Ls / dt_s, "unit": "verified tokens/s", "cores": threads, "kind": "oracle",
             "sample": "batch element 0, one %d-token block (%d grid rows) at P=%d of workload %s, all %d layers, "
                       "float64; %.1f s including the per-call bf16->float64 weight conversion" % (
-                          Ls, c["r"], P, c["name"], nl, dt_s)}
+                          Ls, h_blk * c["r"], P, c["name"], nl, dt_s)}
 
 
 def resample_bench(mulo, ctx, kv, c, B, L, P, V, rate, seed, gen):
