@@ -564,9 +564,9 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 // ---- up to 64 tokens (single-token decoding of a few sequences, island passes): weight-streaming kernel ----
 // The work is reading every weight once, so nothing is staged: a workgroup owns 16 output columns (for
 // gate|up: 16 feed-forward columns = 16 gate rows + 16 up rows), its 8 wavefronts split K, and every lane
-// feeds v_mfma_f32_16x16x32_bf16 straight from global memory.  In that instruction's operand layout the four
-// lanes l16, l16 + 16, l16 + 32, l16 + 48 hold 4 x 8 consecutive k of weight row l16, so one load instruction
-// of a wavefront reads 64 contiguous bytes of each of 16 rows: whole 64-byte sectors (with the 32-row
+// feeds v_mfma_f32_16x16x32_bf16 from registers loaded straight from global memory.  In that instruction's operand
+// layout the four lanes l16, l16 + 16, l16 + 32, l16 + 48 hold 4 x 8 consecutive k of weight row l16, so one load
+// instruction of a wavefront reads 64 contiguous bytes of each of 16 rows: whole 64-byte sectors (with the 32-row
 // instruction only two lanes share a row, 32 of every 64 bytes fetched per request), and a matrix of N columns
 // gives N / 16 workgroups (256 for the 4096-column projections: one per CU).  The tokens are the instruction's
 // column dimension (columns m >= M are fed zeros), up to four groups of 16; the accumulators come out as
@@ -580,14 +580,21 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     __shared__ float part[8][NA * MT][4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, q = lane >> 4;
+    // Loads use another lane order than the MFMA: lane 4 r + c fetches chunk c (16 bytes) of row r, so that four
+    // ADJACENT lanes read 64 contiguous bytes (one access of the vector L1; in the MFMA's own order, lane 16 c + r,
+    // adjacent lanes sit in different rows and every lane is an access of its own: the L1 then limits the kernel).
+    // Each fetched register is moved to the MFMA's order by a lane permutation (ds_bpermute: lane 16 c + r takes
+    // the value of lane 4 r + c); which k a slot holds is unchanged, hence so is every sum.
+    const int lrow = lane >> 2, lchunk = lane & 3;
+    const int from_lane = (4 * l16 + q) << 2;   // byte address of the source lane for ds_bpermute
     const int n_blk = blockIdx.x * 16;     // first output column (gate|up: first feed-forward column)
     const int steps = g.K / 32, per = (steps + 7) / 8;
     const int s0 = wave * per, s1 = s0 + per < steps ? s0 + per : steps;
 
-    // weight row(s) of this lane
+    // weight row(s) this lane fetches
     const bf16* w[NA];
     {
-        int r = n_blk + l16;
+        int r = n_blk + lrow;
         if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
             const int seg = n_blk / g.d;                       // a block never straddles q | k | v (d % 16 == 0)
             w[0] = (seg == 0 ? g.W0 : seg == 1 ? g.W1 : g.W2) + (int64_t)(r - seg * g.d) * g.K;
@@ -601,16 +608,24 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
             w[0] = g.W0 + (int64_t)r * g.K;
         }
     }
-    // token row(s) of this lane: lanes past M read token 0's row and feed zeros
+    // token row(s) this lane fetches (rows past M: token 0's row) and whether the token it feeds to the MFMA exists
     const bf16* xp[MT];
     bool has_x[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         has_x[t] = t * 16 + l16 < g.M;
-        xp[t] = g.A + (int64_t)(has_x[t] ? t * 16 + l16 : 0) * g.K + q * 8;
+        xp[t] = g.A + (int64_t)(t * 16 + lrow < g.M ? t * 16 + lrow : 0) * g.K + lchunk * 8;
     }
 #pragma unroll
-    for (int i = 0; i < NA; ++i) w[i] += q * 8;
+    for (int i = 0; i < NA; ++i) w[i] += lchunk * 8;
+    auto to_mfma_order = [&](u32x4 v) {
+        u32x4 r;
+        r.x = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.x);
+        r.y = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.y);
+        r.z = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.z);
+        r.w = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.w);
+        return r;
+    };
 
     f32x4v acc[NA][MT];
 #pragma unroll
@@ -633,13 +648,16 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const bool in_slice = sb + u < s1;
+            bf16x8 wf[NA];
+#pragma unroll
+            for (int i = 0; i < NA; ++i) wf[i] = __builtin_bit_cast(bf16x8, to_mfma_order(wv[i][u]));
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const bf16x8 xf = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xv[t][u] : zero);
+                const u32x4 xm = to_mfma_order(xv[t][u]);   // every lane takes part: not under the lane-dependent select
+                const bf16x8 xf = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xm : zero);
 #pragma unroll
                 for (int i = 0; i < NA; ++i)
-                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[i][u]), xf,
-                                                                        acc[i][t], 0, 0, 0);
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf, acc[i][t], 0, 0, 0);
             }
         }
     }
