@@ -179,7 +179,8 @@ MULO_API mulo_status mulo_upsample_draft(mulo_ctx *ctx, int32_t B, int32_t h, in
 /* Step 3 (Sec. 3.2; Alg. 1 Step 3).  One forward pass of the target over L
  * inputs per sequence against cache rows [0, P); logits[b, j, :] is the
  * next-token logit vector AFTER input j.  Writes cache rows [P, P+L).
- *   in_tokens  device int32 [B, L] (ids outside [0, vocab) are clamped)
+ *   in_tokens  device int32 [B, L] (ids outside [0, vocab) are clamped to the nearest valid id, silently: the
+ *              kernels never fault on a bad id, and no output flags it; the same holds for draft tokens)
  *   in_embeds  device, model dtype [B, L, d], or NULL; when given it replaces
  *              the embedding lookup (conditioning prefixes)
  *   logits     device float32 [B, L, vocab] (out)
@@ -261,7 +262,7 @@ MULO_API mulo_status mulo_rejection_islands(mulo_ctx *ctx, int32_t B, int32_t W,
  * layer and attends to rows [0, P), to its own row, and to the earlier rows P+v of its block whose position is
  * settled: not marked (the verification pass's row) or re-drawn in an earlier pass.  Marked positions not yet
  * re-drawn are hidden.  (Which context a concurrently evaluated position may use is not spelled out by the paper;
- * this is the reading "the accepted tokens are a valid and sufficient context".)  One island that covers everything
+ * this is a reading of Sec. 3.4: only settled positions are context.)  One island that covers everything
  * from its first position on gives exactly mulo_resample_sequential.  The cache rows P .. P+L-1 must hold the
  * verification pass over the block.  bf16 models only.
  *   n_passes    size of the largest island over the batch, max_islands >= the largest number of islands of a

@@ -375,12 +375,8 @@ template <int DH, int BQ, int BKV, int NTH>
 void run_attn_cfg(const AttnArgs& a, hipStream_t st) {
     auto kern = k_attn_bf16<DH, BQ, BKV, NTH>;
     const size_t lds = (size_t)2 * (BKV * (DH + 8) + DH * (BKV + 8)) * sizeof(bf16);
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    static int attr_state = 0;
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, &attr_state)) return;
     hipLaunchKernelGGL(kern, dim3(((a.L + BQ - 1) / BQ) * a.nh * a.B * a.nsplit), dim3(NTH), lds, st, a);
     if (a.nsplit > 1) hipLaunchKernelGGL(k_attn_combine<DH>, dim3(a.B * a.nh * a.L), dim3(DH), 0, st, a);
 }

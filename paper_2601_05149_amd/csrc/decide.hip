@@ -195,6 +195,14 @@ __global__ __launch_bounds__(TPB) void k_copy(const float4* __restrict__ in, flo
         out[i] = in[i];
 }
 
+// dst[b, :] = src[b, :] for rows of V floats, destination rows dst_stride floats apart
+__global__ __launch_bounds__(TPB) void k_copy_rows_strided(const float4* __restrict__ src, float* __restrict__ dst,
+                                                           int nv4, int64_t dst_stride) {
+    const int b = blockIdx.y;
+    float4* d = reinterpret_cast<float4*>(dst + b * dst_stride);
+    for (int i = blockIdx.x * TPB + threadIdx.x; i < nv4; i += gridDim.x * TPB) d[i] = src[(int64_t)b * nv4 + i];
+}
+
 // x~[b, (rI+a) W + rJ+c] = y~[b, I w + J];  q_row[u] = (i_u / r) w + j_u / r
 __global__ __launch_bounds__(TPB) void k_upsample_tokens(const int32_t* __restrict__ lo,
                                                          int32_t* __restrict__ hi,
@@ -632,6 +640,13 @@ void launch_copy_rows(const float* in, float* out, int64_t n_floats, hipStream_t
                        reinterpret_cast<float4*>(out), n4);
 }
 
+void launch_copy_rows_strided(const float* src, float* dst, int B, int V, int64_t dst_stride, hipStream_t st) {
+    if (B <= 0 || V <= 0) return;
+    const int nv4 = V >> 2;
+    hipLaunchKernelGGL(k_copy_rows_strided, dim3((nv4 + TPB - 1) / TPB < 64 ? (nv4 + TPB - 1) / TPB : 64, B), dim3(TPB), 0, st,
+                       reinterpret_cast<const float4*>(src), dst, nv4, dst_stride);
+}
+
 void launch_upsample_tokens(const int32_t* draft_tokens, int32_t* tokens_hi, int32_t* q_row, int B,
                             int h, int w, int r, hipStream_t st) {
     const int64_t n = (int64_t)B * h * r * w * r;
@@ -652,7 +667,9 @@ void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t*
 }
 
 void launch_islands(const uint8_t* mask, int32_t* island, int32_t* rank, int32_t* counts, int B, int W, int n0, int L,
-                    hipStream_t st) {
+                    hipStream_t st) {   // L <= 16384 (the caller checks): one label per position in LDS
+    static int attr_state = 0;
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(k_islands), 16384 * (int)sizeof(int), &attr_state)) return;
     hipLaunchKernelGGL(k_islands, dim3(B), dim3(TPB), (size_t)L * sizeof(int), st, mask, island, rank, counts, W, n0, L);
 }
 
@@ -682,12 +699,8 @@ void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* to
 }
 
 void launch_decide_finish(const DecideArgs& a, hipStream_t st) {   // a.L <= 131072 (the caller checks): flags in LDS
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_decide_finish),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
-        attr_set = true;
-    }
+    static int attr_state = 0;
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(k_decide_finish), 131072, &attr_state)) return;
     hipLaunchKernelGGL(k_decide_finish, dim3(a.B), dim3(TPB), (size_t)a.L, st, a);
 }
 

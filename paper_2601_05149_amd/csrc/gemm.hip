@@ -547,12 +547,8 @@ template <int BM, int BN, int WGM, int WGN, int EPI, int BKT = 64, bool FULL = f
 void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream_t st) {
     auto kern = k_gemm_bf16<BM, BN, WGM, WGN, EPI, BKT, FULL>;
     const size_t lds = (size_t)2 * (BM + BN) * (BKT + 8) * sizeof(bf16);
-    static bool attr_set = false;  // one context per process configures each instantiation once
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    static int attr_state = 0;  // each instantiation is configured once per process
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, &attr_state)) return;
     const int tiles_m = (g.M + BM - 1) / BM, total = tiles_m * tiles_n;
     const int resident = cu_count() * blocks_per_cu;
     g.tiles_n = tiles_n;

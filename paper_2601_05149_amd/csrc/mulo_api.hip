@@ -11,6 +11,24 @@
 
 using namespace mulo;
 
+namespace mulo {
+namespace {
+hipError_t g_config_error = hipSuccess;   // first failed configuration call since the last check_launch()
+}
+void note_hip_error(hipError_t e) {
+    if (e != hipSuccess && g_config_error == hipSuccess) g_config_error = e;
+}
+bool ensure_dynamic_lds(const void* kern, int bytes, int* state) {
+    if (*state == 0) {
+        const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        *state = e == hipSuccess ? 1 : -1;
+        if (e != hipSuccess) (void)hipGetLastError();
+    }
+    if (*state < 0) note_hip_error(hipErrorInvalidValue);
+    return *state > 0;
+}
+}  // namespace mulo
+
 struct mulo_ctx {
     mulo_model_cfg cfg;
     mulo_weights w;
@@ -90,15 +108,12 @@ struct ProfScope {
 };
 #define PROF(cls) ProfScope prof_scope_##__LINE__(c, cls)
 
-mulo_status check_launch() { return hip_ok(hipGetLastError()) ? MULO_OK : MULO_ERR_HIP; }
-
-mulo_status check_forward_args(const mulo_ctx* ctx, const mulo_kv* kv, int B, int L, int P) {
-    if (!ctx || !kv || !kv->k || !kv->v) return MULO_ERR_NULL;
-    if (B < 1 || L < 1 || P < 0) return MULO_ERR_RANGE;
-    if (B > ctx->cfg.max_batch || L > ctx->cfg.max_block || (int64_t)P + L > ctx->cfg.max_seq)
-        return MULO_ERR_SHAPE;
-    return MULO_OK;
+mulo_status check_launch() {
+    const bool configured = g_config_error == hipSuccess;
+    g_config_error = hipSuccess;
+    return hip_ok(hipGetLastError()) && configured ? MULO_OK : MULO_ERR_HIP;
 }
+
 
 // Scattered single-token queries (island-parallel re-sampling): the "block" is L slots per sequence, slot j of
 // sequence b sits at cache row pos_tab[b * L + j] (< 0: unused); rows P0 + t of a sequence with hide[b, t] set
@@ -185,8 +200,8 @@ void enqueue_decide(mulo_ctx* c, const DecideArgs& a) {
     { PROF(MULO_PROF_MASK_SAMPLE); launch_mask_sample(a, c->st); }
 }
 
-void fill_decide(DecideArgs& a, const mulo_ctx* ctx, int B, const mulo_step_params* p) {
-    a.B = B; a.L = p->L; a.V = ctx->cfg.vocab;
+void fill_decide(DecideArgs& a, int vocab, float* rowmax, float* rowinv, int B, const mulo_step_params* p) {
+    a.B = B; a.L = p->L; a.V = vocab;
     a.H = p->H; a.W = p->W; a.n0 = p->n0;
     a.rho = p->radius < 0 ? -1 : p->radius * p->expand;
     a.pool_k = p->pool_k < 1 ? 1 : p->pool_k;
@@ -199,8 +214,8 @@ void fill_decide(DecideArgs& a, const mulo_ctx* ctx, int B, const mulo_step_para
     a.key1 = (uint32_t)(p->seed >> 32);
     a.ctr_lo = (uint32_t)(p->rng_counter & 0xFFFFFFFFu);
     a.ctr_hi24 = (uint32_t)((p->rng_counter >> 32) & 0xFFFFFFu);
-    a.rowmax = ctx->rowmax;
-    a.rowinv = ctx->rowinv;
+    a.rowmax = rowmax;
+    a.rowinv = rowinv;
 }
 
 }  // namespace
@@ -240,8 +255,17 @@ mulo_status mulo_check_model_cfg(const mulo_model_cfg* c) {
     return MULO_OK;
 }
 
+namespace {
+mulo_status check_step_params_raw(int vocab, int max_batch, int max_block, int32_t B, const mulo_step_params* p);
+}
+
 mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mulo_step_params* p) {
     if (!c || !p) return MULO_ERR_NULL;
+    return check_step_params_raw(c->vocab, c->max_batch, c->max_block, B, p);
+}
+
+namespace {
+mulo_status check_step_params_raw(int vocab, int max_batch, int max_block, int32_t B, const mulo_step_params* p) {
     if (B < 1 || p->H < 1 || p->W < 1 || p->L < 1 || p->n0 < 0 || p->radius < -1 || p->expand < 0 ||
         p->pool_k < 1 || p->resample_mode < 0 || p->resample_mode > 2 ||
         (p->accept_mode != MULO_ACCEPT_RATIO && p->accept_mode != MULO_ACCEPT_TAU) ||
@@ -249,13 +273,14 @@ mulo_status mulo_check_step_params(const mulo_model_cfg* c, int32_t B, const mul
         !(p->cfg_scale >= 0.f && p->cfg_scale <= 1.0e6f))
         return MULO_ERR_RANGE;
     if ((int64_t)p->radius * p->expand > 4096) return MULO_ERR_RANGE;
-    if ((p->cfg_scale > 0.f ? 2 * (int64_t)B : (int64_t)B) > c->max_batch || p->L > c->max_block) return MULO_ERR_SHAPE;
+    if ((p->cfg_scale > 0.f ? 2 * (int64_t)B : (int64_t)B) > max_batch || p->L > max_block) return MULO_ERR_SHAPE;
     if (p->L > 131072) return MULO_ERR_UNSUPPORTED;   // the accept flags of a block are staged in LDS
     if (p->L % p->W || p->n0 % p->W || (int64_t)p->n0 + p->L > (int64_t)p->H * p->W) return MULO_ERR_SHAPE;
     if (p->pool_k > 1 && !p->nbr) return MULO_ERR_NULL;
-    if (p->pool_k > c->vocab) return MULO_ERR_RANGE;
+    if (p->pool_k > vocab) return MULO_ERR_RANGE;
     return MULO_OK;
 }
+}  // namespace
 
 uint64_t mulo_workspace_bytes(const mulo_model_cfg* cfg) {
     if (mulo_check_model_cfg(cfg) != MULO_OK) return 0;
@@ -370,7 +395,7 @@ mulo_status mulo_accept_local_resample(mulo_ctx* ctx, int32_t B, const mulo_step
     if (!q && !(p->accept_mode == MULO_ACCEPT_TAU && p->resample_mode == 2)) return MULO_ERR_NULL;
     if (q_batch_stride < 0) return MULO_ERR_RANGE;
     DecideArgs a{};
-    fill_decide(a, ctx, B, p);
+    fill_decide(a, ctx->cfg.vocab, ctx->rowmax, ctx->rowinv, B, p);
     a.logits = logits; a.q = q; a.q_row = q_row; a.q_batch_stride = q_batch_stride;
     a.logits_u = p->cfg_scale > 0.f ? logits + (int64_t)B * p->L * ctx->cfg.vocab : nullptr;
     a.draft_tokens = draft_tokens; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
@@ -410,7 +435,7 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     enqueue_forward(ctx, kv, B2, L, P, ctx->inputs, nullptr, lg);
     // Steps 4-5 + residual re-draw
     DecideArgs a{};
-    fill_decide(a, ctx, B, p);
+    fill_decide(a, ctx->cfg.vocab, ctx->rowmax, ctx->rowinv, B, p);
     a.logits = lg; a.q = need_q ? ctx->q_lo : nullptr; a.q_row = ctx->q_row; a.q_batch_stride = (int64_t)n_lo * V;
     a.logits_u = cfg_on ? lg + (int64_t)B * L * V : nullptr;
     a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
@@ -433,9 +458,7 @@ mulo_status mulo_resample_sequential(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int3
         { PROF(MULO_PROF_OTHER); launch_seq_input(prev_tokens, tokens, ctx->inputs, B, L, u, ctx->st); }
         enqueue_forward(ctx, kv, B, 1, P + u, ctx->inputs, nullptr, ctx->logits);
         { PROF(MULO_PROF_MASK_SAMPLE); launch_seq_draw(ctx->logits, mask, tokens, B, L, V, u, seed, rng_counter, ctx->st); }
-        if (logits)
-            for (int b = 0; b < B; ++b)
-                launch_copy_rows(ctx->logits + (int64_t)b * V, logits + ((int64_t)b * L + u) * V, V, ctx->st);
+        if (logits) launch_copy_rows_strided(ctx->logits, logits + (int64_t)u * V, B, V, (int64_t)L * V, ctx->st);
     }
     return check_launch();
 }

@@ -7,6 +7,13 @@
 
 namespace mulo {
 
+// A HIP call made while configuring a kernel (not a launch) failed: the entry point that is running returns
+// MULO_ERR_HIP.  The launcher that notes an error does not launch.
+void note_hip_error(hipError_t e);
+// Raises the dynamic-LDS limit of `kern` to `bytes` once per process (state: 0 = not tried, 1 = done, -1 = failed);
+// false, with the error noted, when the runtime refuses.
+bool ensure_dynamic_lds(const void* kern, int bytes, int* state);
+
 // ---- decision stage (decide.hip) -------------------------------------------
 struct DecideArgs {
     int B, L, V;
@@ -36,6 +43,8 @@ struct DecideArgs {
 };
 void launch_softmax_rows(const float* in, float* out, int64_t rows, int V, hipStream_t st);
 void launch_copy_rows(const float* in, float* out, int64_t n_floats, hipStream_t st);
+// dst[b * dst_stride + c] = src[b * V + c] for B rows of V floats (V a multiple of 4)
+void launch_copy_rows_strided(const float* src, float* dst, int B, int V, int64_t dst_stride, hipStream_t st);
 void launch_upsample_tokens(const int32_t* draft_tokens, int32_t* tokens_hi, int32_t* q_row, int B,
                             int h, int w, int r, hipStream_t st);
 void launch_gather_rows(const float* q_lo, const int32_t* q_row, float* q_hi, int B, int n_lo,
