@@ -207,6 +207,26 @@ MULO_API mulo_status mulo_accept_local_resample(mulo_ctx *ctx, int32_t B, const 
                                        int32_t *tokens_out, uint8_t *accept, uint8_t *mask,
                                        int32_t *t0, int32_t *stats, float *p_probs);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc (mulo_create allocates a workspace, so such a caller may have no context).  The decision
+ * stage of mulo_accept_local_resample without a context: same arguments and same results bit for bit, with the
+ * vocabulary size and the HIP stream (a hipStream_t, NULL = the default stream) passed directly.  The row
+ * statistics that the accept kernel leaves for the re-draw kernel live in a static device array of the library
+ * (2 * MULO_STATIC_MAX_ROWS floats = 512 KiB on every GPU the library runs on, held until the process ends).
+ * The call allocates and frees nothing and synchronises with nothing; it runs on the current HIP device.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race
+ * and give undefined decisions; calls on one stream are ordered and safe.  Nothing of an earlier call's contents
+ * is read.
+ * Errors: as mulo_accept_local_resample, plus B * L > MULO_STATIC_MAX_ROWS -> MULO_ERR_SHAPE; vocab < 4 ->
+ * MULO_ERR_RANGE; vocab not a multiple of 4 or > 262144 -> MULO_ERR_UNSUPPORTED; the array's address cannot be
+ * obtained -> MULO_ERR_HIP. */
+#define MULO_STATIC_MAX_ROWS 65536
+MULO_API mulo_status mulo_accept_local_resample_static(void *hip_stream, int32_t vocab, int32_t B,
+                                              const mulo_step_params *p, const float *logits, const float *q,
+                                              const int32_t *q_row, int64_t q_batch_stride,
+                                              const int32_t *draft_tokens, int32_t *tokens_out, uint8_t *accept,
+                                              uint8_t *mask, int32_t *t0, int32_t *stats, float *p_probs);
+
 /* The whole step for one block: up-sample the h_blk x w low-resolution rows
  * behind the block (h_blk * r * w * r == L), run the target over the inputs
  * [prev, x~_0 .. x~_{L-2}] so that logit row j is p for draft position j, then

@@ -17,7 +17,7 @@ STATUS_NAMES = {0: "MULO_OK", 1: "MULO_ERR_NULL", 2: "MULO_ERR_SHAPE", 3: "MULO_
                 4: "MULO_ERR_ALLOC", 5: "MULO_ERR_HIP", 6: "MULO_ERR_UNSUPPORTED"}
 EXPORTS = ["mulo_status_string", "mulo_check_model_cfg", "mulo_check_step_params", "mulo_workspace_bytes",
            "mulo_create", "mulo_destroy", "mulo_upsample_draft", "mulo_verify_forward",
-           "mulo_accept_local_resample", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_resample_islands", "mulo_profile",
+           "mulo_accept_local_resample", "mulo_accept_local_resample_static", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_resample_islands", "mulo_profile",
            "mulo_profile_read"]
 
 
@@ -74,6 +74,7 @@ def load_library():
     lib.mulo_upsample_draft.argtypes = [P, I32, I32, I32, I32, P, I32, P, P, P, P, P]
     lib.mulo_verify_forward.argtypes = [P, C.POINTER(KV), I32, I32, I32, P, P, P]
     lib.mulo_accept_local_resample.argtypes = [P, I32, C.POINTER(StepParams), P, P, P, I64, P, P, P, P, P, P, P]
+    lib.mulo_accept_local_resample_static.argtypes = [P, I32, I32, C.POINTER(StepParams), P, P, P, I64, P, P, P, P, P, P, P]
     lib.mulo_verify_step.argtypes = [P, C.POINTER(KV), I32, I32, C.POINTER(StepParams), I32, I32, I32, P, I32,
                                      P, P, P, P, P, P, P, P, P]
     lib.mulo_resample_sequential.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P]
@@ -187,6 +188,21 @@ def mulo_accept_local_resample(ctx, B, params, logits, q, q_row, q_batch_stride,
         ctx.handle, B, C.byref(params), _ptr(logits, f32), _ptr(q, f32, True), _ptr(q_row, i32, True),
         int(q_batch_stride), _ptr(draft_tokens, i32), _ptr(tokens_out, i32), _ptr(accept, u8), _ptr(mask, u8),
         _ptr(t0, i32), _ptr(stats, i32), _ptr(p_probs, f32, True)), "mulo_accept_local_resample")
+
+
+MULO_STATIC_MAX_ROWS = 65536
+
+
+def mulo_accept_local_resample_static(vocab, B, params, logits, q, q_row, q_batch_stride, draft_tokens, tokens_out,
+                                      accept, mask, t0, stats, p_probs=None, stream=None):
+    """The decision stage without a context (allocates nothing); stream: a raw hipStream_t or None for
+    torch's current stream."""
+    f32, i32, u8 = torch.float32, torch.int32, torch.uint8
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _check(load_library().mulo_accept_local_resample_static(
+        C.c_void_p(st), vocab, B, C.byref(params), _ptr(logits, f32), _ptr(q, f32, True), _ptr(q_row, i32, True),
+        int(q_batch_stride), _ptr(draft_tokens, i32), _ptr(tokens_out, i32), _ptr(accept, u8), _ptr(mask, u8),
+        _ptr(t0, i32), _ptr(stats, i32), _ptr(p_probs, f32, True)), "mulo_accept_local_resample_static")
 
 
 def mulo_verify_step(ctx, kv, B, P, params, h_blk, w, r, draft, input_is_probs, draft_tokens, prev_tokens,

@@ -11,6 +11,13 @@
 
 using namespace mulo;
 
+// Scratch of mulo_accept_local_resample_static, the entry point for callers that cannot allocate: the row maximum
+// and the inverse row sum of the target softmax, MULO_STATIC_MAX_ROWS floats each, which the accept kernel leaves
+// for the re-draw kernel.  Every GPU the library runs on holds its own copy at its own address until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress: kernels, copies and memsets get the
+// device address that call returns (static_scratch below), never the name.
+static __device__ __align__(256) float scratch[2 * MULO_STATIC_MAX_ROWS];
+
 namespace mulo {
 namespace {
 hipError_t g_config_error = hipSuccess;   // first failed configuration call since the last check_launch()
@@ -114,6 +121,30 @@ mulo_status check_launch() {
     return hip_ok(hipGetLastError()) && configured ? MULO_OK : MULO_ERR_HIP;
 }
 
+// Device address of `scratch` on the current device, looked up once per device (with that device current).
+constexpr int MAX_DEVICES = 64;
+float* static_scratch() {
+    static float* per_device[MAX_DEVICES] = {};
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev)) || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)))) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        per_device[dev] = static_cast<float*>(p);
+    }
+    return per_device[dev];
+}
+
+mulo_status check_forward_args(const mulo_ctx* ctx, const mulo_kv* kv, int B, int L, int P) {
+    if (!ctx || !kv || !kv->k || !kv->v) return MULO_ERR_NULL;
+    if (B < 1 || L < 1 || P < 0) return MULO_ERR_RANGE;
+    if (B > ctx->cfg.max_batch || L > ctx->cfg.max_block || (int64_t)P + L > ctx->cfg.max_seq)
+        return MULO_ERR_SHAPE;
+    return MULO_OK;
+}
 
 // Scattered single-token queries (island-parallel re-sampling): the "block" is L slots per sequence, slot j of
 // sequence b sits at cache row pos_tab[b * L + j] (< 0: unused); rows P0 + t of a sequence with hide[b, t] set
@@ -401,6 +432,37 @@ mulo_status mulo_accept_local_resample(mulo_ctx* ctx, int32_t B, const mulo_step
     a.draft_tokens = draft_tokens; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = p_probs;
     enqueue_decide(ctx, a);
+    return check_launch();
+}
+
+mulo_status mulo_accept_local_resample_static(void* hip_stream, int32_t vocab, int32_t B, const mulo_step_params* p,
+                                              const float* logits, const float* q, const int32_t* q_row,
+                                              int64_t q_batch_stride, const int32_t* draft_tokens, int32_t* tokens_out,
+                                              uint8_t* accept, uint8_t* mask, int32_t* t0, int32_t* stats,
+                                              float* p_probs) {
+    if (!p || !logits || !draft_tokens || !tokens_out || !accept || !mask || !t0 || !stats) return MULO_ERR_NULL;
+    if (vocab < 4 || B < 1) return MULO_ERR_RANGE;
+    if ((vocab & 3) || vocab > 262144) return MULO_ERR_UNSUPPORTED;
+    const int64_t seqs = p->cfg_scale > 0.f ? 2 * (int64_t)B : (int64_t)B;
+    const mulo_status s = check_step_params_raw(vocab, seqs > 0x7fffffff ? 0x7fffffff : (int)seqs, p->L, B, p);
+    if (s != MULO_OK) return s;
+    if ((int64_t)B * p->L > MULO_STATIC_MAX_ROWS) return MULO_ERR_SHAPE;   // the row statistics must fit the static scratch
+    if (!q && !(p->accept_mode == MULO_ACCEPT_TAU && p->resample_mode == 2)) return MULO_ERR_NULL;
+    if (q_batch_stride < 0) return MULO_ERR_RANGE;
+    float* const sc = static_scratch();
+    if (!sc) return MULO_ERR_HIP;
+    DecideArgs a{};
+    // both halves are written for every row by the accept kernel before the re-draw reads them: nothing of the
+    // last call's contents is used, nothing needs clearing
+    fill_decide(a, vocab, sc, sc + MULO_STATIC_MAX_ROWS, B, p);
+    a.logits = logits; a.q = q; a.q_row = q_row; a.q_batch_stride = q_batch_stride;
+    a.logits_u = p->cfg_scale > 0.f ? logits + (int64_t)B * p->L * vocab : nullptr;
+    a.draft_tokens = draft_tokens; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
+    a.t0 = t0; a.stats = stats; a.p_probs = p_probs;
+    hipStream_t st = (hipStream_t)hip_stream;
+    launch_accept(a, st);
+    launch_decide_finish(a, st);
+    launch_mask_sample(a, st);
     return check_launch();
 }
 

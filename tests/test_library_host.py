@@ -105,3 +105,21 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=300, cwd=root)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr + r.stdout and '"metric"' not in r.stdout
+
+
+def test_static_entry_point_rejects_bad_arguments_before_any_gpu_call(lib):
+    """mulo_accept_local_resample_static checks its arguments on the host first (no device is touched)."""
+    V, B, L = 1024, 1, 64
+    ok = BD.StepParams(H=8, W=8, n0=0, L=L, radius=1, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0, rng_counter=0)
+    one = C.c_void_p(256)       # never dereferenced: every call below fails its checks
+    call = lambda vocab, b, p, logits=one: lib.mulo_accept_local_resample_static(
+        None, vocab, b, p, logits, one, None, L * V, one, one, one, one, one, one, None)
+    assert call(V, B, C.byref(ok), logits=None) == 1
+    assert call(V, B, None) == 1
+    assert call(2, B, C.byref(ok)) == 3
+    assert call(V + 2, B, C.byref(ok)) == 6
+    assert call(V, BD.MULO_STATIC_MAX_ROWS // L + 1, C.byref(ok)) == 2         # more rows than the static scratch
+    bad = BD.StepParams(H=8, W=8, n0=0, L=60, radius=1, expand=1, pool_k=1, nbr=None, resample_mode=0, seed=0, rng_counter=0)
+    assert call(V, B, C.byref(bad)) == 2
+    header = open(os.path.join(ROOT, "include", "mulo.h")).read()
+    assert "#define MULO_STATIC_MAX_ROWS %d" % BD.MULO_STATIC_MAX_ROWS in header
