@@ -300,6 +300,21 @@ MULO_API mulo_status mulo_resample_islands(mulo_ctx *ctx, mulo_kv *kv, int32_t B
                                   const int32_t *prev_tokens, const uint8_t *mask, const int32_t *rank,
                                   int32_t *tokens, float *logits, int32_t *overflow);
 
+/* Test and debugging aid (not part of the method): copies the first `bytes` bytes of one of the context's
+ * workspace buffers, as the last mulo_verify_forward (or step) left it, to dst on the context's stream.  With a
+ * one-layer model these are that layer's intermediate tensors, which is how the tests compare every stage of a
+ * layer with the oracle's.  M = B * L of that call; T = the model dtype.
+ *   MULO_WS_RESIDUAL  float32 [M, d]       residual stream after the last layer
+ *   MULO_WS_NORMED    T [M, d]             output of the last RMSNorm that ran (the final norm)
+ *   MULO_WS_Q         T [B, n_heads, L, head_dim]  rotated queries of the last layer
+ *   MULO_WS_ATTN      T [M, d]             attention output of the last layer (input of the out projection)
+ *   MULO_WS_FFN       T [M, d_ffn]         silu(gate) * up of the last layer (input of the down projection)
+ *   dst  device pointer, at least `bytes` bytes
+ * Errors: unknown buffer -> MULO_ERR_RANGE; bytes not a multiple of 16 or larger than the buffer (sized for
+ * max_batch * max_block tokens) -> MULO_ERR_SHAPE. */
+enum { MULO_WS_RESIDUAL = 0, MULO_WS_NORMED = 1, MULO_WS_Q = 2, MULO_WS_ATTN = 3, MULO_WS_FFN = 4 };
+MULO_API mulo_status mulo_workspace_read(mulo_ctx *ctx, int32_t which, void *dst, uint64_t bytes);
+
 /* Optional per-kernel timing (measurement aid, not part of the method).  While
  * enabled, every kernel launch of the entry points above is bracketed by a pair
  * of HIP events on the context's stream.  mulo_profile_read synchronises the

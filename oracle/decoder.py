@@ -87,10 +87,14 @@ class DecoderOracle:
         return t.to(torch.float64)
 
     @torch.no_grad()
-    def forward(self, tokens, P, embeds=None, taps=None):
+    def forward(self, tokens, P, embeds=None, taps=None, stages=None):
         """tokens: int [B, L]; P: number of valid cache rows; writes cache rows
         P .. P+L-1; returns float64 logits [B, L, V].  taps: optional list that
-        receives a copy of the residual stream entering every layer."""
+        receives a copy of the residual stream entering every layer.  stages:
+        optional dict that receives, per layer (appended to lists), the tensors
+        the device keeps between its kernels: "q" rotated queries [B, L, n_h, d_h],
+        "att" attention output [B, L, d], "hmid" SwiGLU product [B, L, f] (each after
+        its rounding point) and "x_out" the residual stream leaving the layer."""
         cfg = self.cfg
         nl, d, nh, dh = cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
         eps = cfg.get("rms_eps", 1e-5)
@@ -128,6 +132,9 @@ class DecoderOracle:
             xh = self.rb(rmsnorm(x, self._w("ffn_norm", l), eps))
             hmid = self.rb(silu(xh @ self._w("w_gate", l).T) * (xh @ self._w("w_up", l).T))
             x = x + hmid @ self._w("w_down", l).T
+            if stages is not None:
+                for name, t in (("q", q), ("att", a), ("hmid", hmid), ("x_out", x)):
+                    stages.setdefault(name, []).append(t.clone())
         xh = self.rb(rmsnorm(x, self._w("final_norm"), eps))
         return xh @ self._w("lm_head").T
 

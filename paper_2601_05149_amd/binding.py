@@ -17,7 +17,7 @@ STATUS_NAMES = {0: "MULO_OK", 1: "MULO_ERR_NULL", 2: "MULO_ERR_SHAPE", 3: "MULO_
                 4: "MULO_ERR_ALLOC", 5: "MULO_ERR_HIP", 6: "MULO_ERR_UNSUPPORTED"}
 EXPORTS = ["mulo_status_string", "mulo_check_model_cfg", "mulo_check_step_params", "mulo_workspace_bytes",
            "mulo_create", "mulo_destroy", "mulo_upsample_draft", "mulo_verify_forward",
-           "mulo_accept_local_resample", "mulo_accept_local_resample_static", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_resample_islands", "mulo_profile",
+           "mulo_accept_local_resample", "mulo_accept_local_resample_static", "mulo_verify_step", "mulo_resample_sequential", "mulo_rejection_islands", "mulo_resample_islands", "mulo_workspace_read", "mulo_profile",
            "mulo_profile_read"]
 
 
@@ -80,6 +80,7 @@ def load_library():
     lib.mulo_resample_sequential.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P]
     lib.mulo_rejection_islands.argtypes = [P, I32, I32, I32, I32, P, P, P, P]
     lib.mulo_resample_islands.argtypes = [P, C.POINTER(KV), I32, I32, I32, I32, I32, C.c_uint64, C.c_uint64, P, P, P, P, P, P]
+    lib.mulo_workspace_read.argtypes = [P, I32, P, C.c_uint64]
     lib.mulo_profile.argtypes = [P, I32]
     lib.mulo_profile_read.argtypes = [P, C.POINTER(C.c_float), C.POINTER(I32)]
     for n in EXPORTS:
@@ -238,6 +239,15 @@ def mulo_resample_islands(ctx, kv, B, P, L, n_passes, max_islands, seed, rng_cou
         ctx.handle, C.byref(kvs), B, P, L, n_passes, max_islands, C.c_uint64(seed), C.c_uint64(rng_counter),
         _ptr(prev_tokens, i32), _ptr(mask, u8), _ptr(rank, i32), _ptr(tokens, i32), _ptr(logits, f32, True),
         _ptr(overflow, i32, True)), "mulo_resample_islands")
+
+
+MULO_WS_RESIDUAL, MULO_WS_NORMED, MULO_WS_Q, MULO_WS_ATTN, MULO_WS_FFN = range(5)
+
+
+def mulo_workspace_read(ctx, which, dst):
+    """Copy a workspace buffer of the last forward pass into the (contiguous, device) tensor dst."""
+    _check(load_library().mulo_workspace_read(ctx.handle, which, _ptr(dst), dst.numel() * dst.element_size()),
+           "mulo_workspace_read")
 
 
 PROF_CLASSES = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attention", "norm_embed",

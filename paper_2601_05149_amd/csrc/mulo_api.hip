@@ -369,6 +369,24 @@ void mulo_destroy(mulo_ctx* ctx) {
     delete ctx;
 }
 
+mulo_status mulo_workspace_read(mulo_ctx* ctx, int32_t which, void* dst, uint64_t bytes) {
+    if (!ctx || !dst) return MULO_ERR_NULL;
+    const uint64_t M = (uint64_t)ctx->maxM, d = ctx->cfg.d_model, f = ctx->cfg.d_ffn, e = ctx->esz;
+    const void* src = nullptr;
+    uint64_t cap = 0;
+    switch (which) {
+        case MULO_WS_RESIDUAL: src = ctx->x; cap = M * d * 4; break;
+        case MULO_WS_NORMED: src = ctx->xh; cap = M * d * e; break;
+        case MULO_WS_Q: src = ctx->qbuf; cap = M * d * e; break;
+        case MULO_WS_ATTN: src = ctx->att; cap = M * d * e; break;
+        case MULO_WS_FFN: src = ctx->hmid; cap = M * f * e; break;
+        default: return MULO_ERR_RANGE;
+    }
+    if ((bytes & 15) || bytes > cap) return MULO_ERR_SHAPE;
+    launch_copy_rows((const float*)src, (float*)dst, (int64_t)(bytes / 4), ctx->st);
+    return check_launch();
+}
+
 mulo_status mulo_profile(mulo_ctx* ctx, int32_t enable) {
     if (!ctx) return MULO_ERR_NULL;
     if (enable && ctx->prof_ev.empty()) {

@@ -19,15 +19,7 @@ from workloads import generators as G
 
 pytestmark = pytest.mark.gpu
 
-_W7B = {}
-
-
-def weights_7b():
-    if "w" not in _W7B:
-        say("generating 7B-class weights on the host ...")
-        _W7B["w"] = G.make_weights(WC.model("7b"), seed=0)
-        say("... done")
-    return _W7B["w"]
+from tests.cases_7b import hires_case, seeded_cache_rows, weights_7b  # noqa: E402
 
 
 def gpu_forward(ctx, kv, tokens, P, embeds=None):
@@ -212,33 +204,30 @@ def test_forward_7b_first_block_and_teacher_forced_layers():
         del ctx1, kv1
 
 
+def fill_device_cache(kv, m, P, B):
+    """Seeded N(0, 1) rows [0, P) of every batch element, as tests.cases_7b.seeded_cache_rows makes them."""
+    for b in range(B):
+        kb, vb = seeded_cache_rows(m, P, b)                                  # [nl, nh, P, dh]
+        kv[0][:, b, :, :P] = kb.to(DEV)
+        kv[1][:, b, :, :, :P] = vb.permute(0, 1, 3, 2).to(DEV)
+
+
 @pytest.mark.timeout(900)
 def test_forward_7b_hires_full_launch_sampled_sequence():
     """Config-4 launch (B = 4, L = 1024, P = 3200: the largest cache) on the
     device; the oracle recomputes batch element 0 in full.  Cache rows [0, P) are
     seeded N(0, 1) values on both sides (a real prefill of 3200 rows is hours of
-    CPU time)."""
-    c = WC.get("cfg4")
+    CPU time); the inputs are the sigma recipe's provisional up-sampled draft."""
+    h = hires_case()
+    c, P, toks = h["c"], h["P"], h["inp"]
     m, B, L = c["model"], c["B"], c["L"]
-    P = c["max_seq"] - L
-    nl, nh, dh = m["n_layers"], m["n_heads"], m["head_dim"]
     w = weights_7b()
     ctx, cos, sin = make_ctx(m, w, B, c["max_seq"], L)
     kv = mulo.alloc_kv(ctx, DEV)
-    dr, du = pair(m, w, cos, sin, 1, c["max_seq"])
-    for b in range(B):
-        kb = G.random_kv((nl, nh, P, dh), seed=0, tag=2 * b)            # [nl, nh, S, dh]
-        vb = G.random_kv((nl, nh, P, dh), seed=0, tag=2 * b + 1)
-        kv[0][:, b, :, :P] = kb.to(DEV)
-        kv[1][:, b, :, :, :P] = vb.permute(0, 1, 3, 2).to(DEV)
-        if b == 0:
-            for d_ in (dr, du):
-                d_.k[:, 0, :P] = kb.permute(0, 2, 1, 3).to(d_.k.dtype)
-                d_.v[:, 0, :P] = vb.permute(0, 2, 1, 3).to(d_.v.dtype)
-    toks = G.uniform_tokens((B, L), m["vocab"], 0, tag=3)
+    fill_device_cache(kv, m, P, B)
     zg = gpu_forward(ctx, kv, toks, P)
-    say("7B hi-res block, oracle (rounded + exact) on batch element 0 ...")
-    check_bf16_logits("7B hi-res b=0", zg[:1], dr.forward(toks[:1], P).numpy(), du.forward(toks[:1], P).numpy())
+    check_bf16_logits("7B hi-res b=0", zg[:1], h["z_r"], h["z_u"])
+    say("  logits above 2e-2 of the oracle's: %d of %d" % (int((np.abs(zg[:1] - h["z_r"]) > 2e-2).sum()), h["z_r"].size))
     # batch elements are independent: element 3 alone reproduces its rows of the batched launch
     kv1 = (kv[0][:, 3:4].contiguous(), kv[1][:, 3:4].contiguous())
     ctx1, _, _ = make_ctx(m, w, 1, c["max_seq"], L)

@@ -257,3 +257,21 @@ def test_generators_are_seeded_and_shaped():
     lg = np.log(np.array([[0.7, 0.2, 0.1]] * 20000))
     s = G.sample_categorical(lg, seed=0)
     assert np.abs(np.bincount(s, minlength=3) / 20000 - [0.7, 0.2, 0.1]).max() < 0.02
+
+
+def test_rope_table_every_frequency_is_the_closed_form():
+    """The rotary table is an input shared by the oracle and the device, so it is pinned on its own: pair m of a
+    head turns by pos * 10000^(-2 m / d_h) (Python floats, element by element, no vectorised helper in common
+    with the generator), for every m and a spread of positions up to the longest cache of the workloads."""
+    for dh in (8, 64, 128):
+        S = 4224
+        cos, sin = G.rope_table(S, dh)
+        assert cos.shape == (S, dh // 2) and sin.shape == (S, dh // 2) and cos.dtype == np.float32
+        for pos in (0, 1, 2, 7, 128, 1855, 3199, 4223):
+            for mm in range(dh // 2):
+                ang = pos * (10000.0 ** (-2.0 * mm / dh))
+                assert abs(float(cos[pos, mm]) - math.cos(ang)) < 1e-6, (dh, pos, mm)
+                assert abs(float(sin[pos, mm]) - math.sin(ang)) < 1e-6, (dh, pos, mm)
+    # the slowest pair of a 128-wide head: theta = 10000^(-126/128), a quarter turn takes about 14 000 positions
+    cos, sin = G.rope_table(8, 128)
+    assert abs(float(sin[1, 63]) - 10000.0 ** (-126.0 / 128.0)) < 1e-9
