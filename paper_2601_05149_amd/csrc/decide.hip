@@ -7,6 +7,7 @@
 // codebook with wavefront shuffles, so every logit is read from memory once in
 // the accept pass and once more (with the draft row) only for marked positions.
 #include "mulo_internal.h"
+#include "row_parts.h"
 
 namespace mulo {
 
@@ -69,9 +70,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 
 // exp(z - m) with one hardware exp2; no contraction so every kernel that
 // evaluates it gets the same bits.
-__device__ __forceinline__ float expm(float z, float m) {
-    return __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(z, m), LOG2E));
-}
+__device__ __forceinline__ float expm(float z, float m) { return rowparts::expm(z, m); }
 __device__ __forceinline__ float prob(float z, float m, float inv) {
     return __fmul_rn(expm(z, m), inv);
 }
@@ -239,11 +238,36 @@ __global__ void k_shift_inputs(const int32_t* __restrict__ prev, const int32_t* 
 // ---- Step 4: softmax statistics + accept test, one workgroup per position ---
 __device__ __forceinline__ int clamp_tok(int t, int V) { return t < 0 ? 0 : (t >= V ? V - 1 : t); }
 
-template <int NV4>
+// The accept test of one position, by one lane: Eq. 1 without the division (u q < pbar), or the threshold rule of
+// Eq. 5 (pbar >= tau); leaves the row statistics for the re-draw kernel and parks the near-tie flag in the mask
+// array until k_decide_finish has counted it (per-row atomics on the few counters of a sequence cost a quarter of
+// the accept kernel's time).
+__device__ __forceinline__ void accept_row(const DecideArgs& a, int64_t row, int b, int t, float qt, float pbar,
+                                           float m, float inv) {
+    const uint32_t w0 = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24, a.key0, a.key1);
+    const float u = (float)(w0 >> 8) * 5.9604644775390625e-08f;  // 2^-24, exact
+    // the threshold rule is written as "tau' < pbar or equal" through the same comparison with uq := tau
+    const bool tau_rule = a.accept_mode == 1;
+    const float uq = tau_rule ? a.tau : __fmul_rn(u, qt);
+    const bool ok = tau_rule ? pbar >= uq : uq < pbar;
+    a.accept[row] = ok ? 1 : 0;
+    a.rowmax[row] = m;
+    a.rowinv[row] = inv;
+    a.mask[row] = fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, tau_rule ? a.tau : qt) ? 1 : 0;
+}
+
+constexpr int MAX_PARTS = 2048;   // 128 codebook entries per part -> V <= 262144
+
+// One workgroup per position.  The row is read once: lane `tid` of pass k owns run 256 k + tid (8 consecutive logits),
+// so the 16 lanes of a part sit next to each other, the two halves of the part on the even and the odd lanes; the
+// part statistics are formed with lane exchanges in the order row_parts.h fixes, left in LDS, and merged by the
+// first wavefront.
 __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
+    __shared__ float2 parts[MAX_PARTS];
     __shared__ float red[WAVES];
+    __shared__ float2 s_stat;
     const int64_t row = blockIdx.x;
-    const int b = row / a.L, t = row % a.L, tid = threadIdx.x;
+    const int b = row / a.L, t = row % a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const Guided z{a.logits + row * a.V, a.logits_u ? a.logits_u + row * a.V : nullptr, a.cfg_scale};
     // the scalar gathers (draft token -> its logit and its draft probability) are issued first, so that
     // their chained latency is hidden behind the streaming of the row
@@ -256,11 +280,37 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
         }
         ztok = z.at(tok);
     }
-    RowRegs<NV4> rr;
-    float m, inv;
-    row_stats<NV4>(z, a.V, rr, red, m, inv);
-    if (a.p_probs) row_write_probs<NV4>(z, a.p_probs + row * a.V, a.V, rr, m, inv);
-
+    const int V = a.V, n_parts = (V + rowparts::PART - 1) / rowparts::PART;
+    const float NEG = rowparts::NEG_INF;
+    for (int base = 0; base < n_parts * 16; base += TPB) {
+        const int R = base + tid;                       // run of 8 logits; V is a multiple of 4
+        const int n_valid = V - R * 8 >= 8 ? 8 : (V - R * 8 >= 4 ? 4 : 0);
+        float zz[8];
+        const float4 lo = n_valid >= 4 ? z.at4(2 * R) : make_float4(NEG, NEG, NEG, NEG);
+        const float4 hi = n_valid >= 8 ? z.at4(2 * R + 1) : make_float4(NEG, NEG, NEG, NEG);
+        zz[0] = lo.x; zz[1] = lo.y; zz[2] = lo.z; zz[3] = lo.w; zz[4] = hi.x; zz[5] = hi.y; zz[6] = hi.z; zz[7] = hi.w;
+        float m = fmaxf(fmaxf(fmaxf(zz[0], zz[1]), fmaxf(zz[2], zz[3])), fmaxf(fmaxf(zz[4], zz[5]), fmaxf(zz[6], zz[7])));
+        m = fmaxf(m, __shfl_xor(m, 2));                 // the 8 runs of a half: lanes 2 apart
+        m = fmaxf(m, __shfl_xor(m, 4));
+        m = fmaxf(m, __shfl_xor(m, 8));
+        float s = rowparts::run_sum(zz, m, n_valid);
+        s = __fadd_rn(s, __shfl_xor(s, 2));             // ((t0+t1)+(t2+t3))+((t4+t5)+(t6+t7))
+        s = __fadd_rn(s, __shfl_xor(s, 4));
+        s = __fadd_rn(s, __shfl_xor(s, 8));
+        const float2 ps = rowparts::merge_halves(m, s, __shfl_xor(m, 1), __shfl_xor(s, 1));
+        if ((tid & 15) == 0 && (R >> 4) < n_parts) parts[R >> 4] = ps;
+    }
+    __syncthreads();
+    if (wv == 0) {
+        const float2 st = rowparts::combine_parts(parts, n_parts, lane);
+        if (lane == 0) s_stat = st;
+    }
+    __syncthreads();
+    const float m = s_stat.x, inv = 1.0f / s_stat.y;
+    if (a.p_probs) {
+        RowRegs<0> none;
+        row_write_probs<0>(z, a.p_probs + row * a.V, a.V, none, m, inv);
+    }
     float pbar;
     if (a.pool_k <= 1) {
         pbar = prob(ztok, m, inv);
@@ -270,20 +320,29 @@ __global__ __launch_bounds__(TPB) void k_accept(const DecideArgs a) {
             acc += prob(z.at(clamp_tok(a.nbr[(int64_t)tok * a.pool_k + i], a.V)), m, inv);
         pbar = block_sum(acc, red);
     }
-    if (tid == 0) {
-        const uint32_t w0 = philox_word0((uint32_t)t, (uint32_t)b, a.ctr_lo, a.ctr_hi24, a.key0, a.key1);
-        const float u = (float)(w0 >> 8) * 5.9604644775390625e-08f;  // 2^-24, exact
-        // Eq. 1 without the division: u q < pbar; threshold rule (Eq. 5): pbar >= tau, written as
-        // "tau' < pbar or equal" through the same comparison with uq := tau
-        const bool tau_rule = a.accept_mode == 1;
-        const float uq = tau_rule ? a.tau : __fmul_rn(u, qt);
-        const bool ok = tau_rule ? pbar >= uq : uq < pbar;
-        a.accept[row] = ok ? 1 : 0;
-        a.rowmax[row] = m;
-        a.rowinv[row] = inv;
-        // near-tie flag, parked in the mask array until k_decide_finish has counted it (per-row atomics on the
-        // few counters of a sequence cost a quarter of this kernel's time)
-        a.mask[row] = fabsf(__fsub_rn(pbar, uq)) < __fmul_rn(NEAR_TIE, tau_rule ? a.tau : qt) ? 1 : 0;
+    if (tid == 0) accept_row(a, row, b, t, qt, pbar, m, inv);
+}
+
+// The same test when the lm-head GEMM has already left the parts of every row (a verification step): one
+// wavefront per position merges them and gathers the draft token's logit; the row of logits is not read again.
+__global__ __launch_bounds__(TPB) void k_accept_parts(const DecideArgs a, const float2* __restrict__ parts, int n_parts) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * WAVES + wv;
+    if (row >= (int64_t)a.B * a.L) return;            // uniform over the wavefront
+    const int b = row / a.L, t = row % a.L;
+    const int tok = clamp_tok(a.draft_tokens[row], a.V);
+    float ztok = 0.f, qt = 0.f;
+    if (lane == 0) {
+        if (a.accept_mode == 0) {
+            const int qr = a.q_row ? a.q_row[t] : t;
+            qt = a.q[b * a.q_batch_stride + (int64_t)qr * a.V + tok];
+        }
+        ztok = a.logits[row * a.V + tok];
+    }
+    const float2 st = rowparts::combine_parts(parts + row * n_parts, n_parts, lane);
+    if (lane == 0) {
+        const float m = st.x, inv = 1.0f / st.y;
+        accept_row(a, row, b, t, qt, prob(ztok, m, inv), m, inv);
     }
 }
 
@@ -615,11 +674,6 @@ template <int NV4>
 void softmax_rows_inst(const float* in, float* out, int64_t rows, int V, hipStream_t st) {
     hipLaunchKernelGGL(k_softmax_rows<NV4>, dim3((unsigned)rows), dim3(TPB), 0, st, in, out, V);
 }
-template <int NV4>
-void accept_inst(const DecideArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(k_accept<NV4>, dim3((unsigned)(a.B * a.L)), dim3(TPB), 0, st, a);
-}
-
 }  // namespace
 
 void launch_softmax_rows(const float* in, float* out, int64_t rows, int V, hipStream_t st) {
@@ -705,12 +759,13 @@ void launch_decide_finish(const DecideArgs& a, hipStream_t st) {   // a.L <= 131
 }
 
 void launch_accept(const DecideArgs& a, hipStream_t st) {
-    if (a.V <= 1024) accept_inst<1>(a, st);
-    else if (a.V <= 2048) accept_inst<2>(a, st);
-    else if (a.V <= 4096) accept_inst<4>(a, st);
-    else if (a.V <= 8192) accept_inst<8>(a, st);
-    else if (a.V <= 16384) accept_inst<16>(a, st);
-    else accept_inst<0>(a, st);
+    hipLaunchKernelGGL(k_accept, dim3((unsigned)(a.B * a.L)), dim3(TPB), 0, st, a);
+}
+
+void launch_accept_from_parts(const DecideArgs& a, const float* parts, int n_parts, hipStream_t st) {
+    const int64_t rows = (int64_t)a.B * a.L;
+    hipLaunchKernelGGL(k_accept_parts, dim3((unsigned)((rows + WAVES - 1) / WAVES)), dim3(TPB), 0, st, a,
+                       reinterpret_cast<const float2*>(parts), n_parts);
 }
 
 void launch_mask_sample(const DecideArgs& a, hipStream_t st) {

@@ -20,6 +20,7 @@
 #include <utility>
 
 #include "mulo_internal.h"
+#include "row_parts.h"
 
 namespace mulo {
 namespace {
@@ -45,6 +46,8 @@ struct GemmArgs {
     int d;                // QK: model width (segment size)
     int tiles_n;          // column tiles of the launch (set by the launcher)
     int tile_n0;          // first column tile of the launch (set by the launcher)
+    float2* parts;        // LOGITS: softmax statistics per 128-column part of every row [M, n_parts], or nullptr
+    int n_parts;
     RopeArgs ra;
 };
 
@@ -183,6 +186,37 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB
             }
         });
         return;
+    }
+    if constexpr (EPI == EPI_LOGITS && TN == rowparts::PART) {
+        // Softmax statistics of the wavefront tile's 128 columns, per token, for the accept test (Sec. 3.1, Eq. 1):
+        // this lane holds half lh of part (tile_n, wn) of token row m, run rr = 2 j + g2 in accumulators
+        // 8 g2 .. 8 g2 + 7 of block j; the other half sits in lane + 32.  Whole tiles only (every column exists).
+        if (g.parts) {
+            static_for<MB>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const int m = m0 + wm * TM + i * 32 + l32;
+                float mx = rowparts::NEG_INF;
+                static_for<NB>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
+                });
+                float t[8];
+                static_for<NB>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+#pragma unroll
+                    for (int g2 = 0; g2 < 2; ++g2) {
+                        float zz[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) zz[e] = acc[i][j][g2 * 8 + e];
+                        t[j * 2 + g2] = rowparts::run_sum(zz, mx, 8);
+                    }
+                });
+                const float sm = rowparts::tree8(t);
+                const float2 ps = rowparts::merge_halves(mx, sm, __shfl_xor(mx, 32), __shfl_xor(sm, 32));
+                if (lh == 0 && m < g.M) g.parts[(int64_t)m * g.n_parts + tile_n * (BN / rowparts::PART) + wn] = ps;
+            });
+        }
     }
     static_for<MB>([&](auto ic) {
         static_for<NBE>([&](auto jc) {
@@ -734,11 +768,12 @@ void run_gemv(const GemmArgs& g, hipStream_t st) {
     else hipLaunchKernelGGL((k_gemv_bf16<EPI, 4>), grid, dim3(512), 0, st, g);
 }
 
+// returns whether the launch ran on the kernels whose wavefront tile is 128 columns wide (whole tiles)
 template <int EPI>
-void dispatch(const GemmArgs& g, hipStream_t st) {
+bool dispatch(const GemmArgs& g, hipStream_t st) {
     if (g.M <= 64 && (EPI != EPI_QK || g.d % 32 == 0)) {   // a handful of tokens: stream the weights
         run_gemv<EPI>(g, st);
-        return;
+        return false;
     }
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
@@ -766,7 +801,9 @@ void dispatch(const GemmArgs& g, hipStream_t st) {
         if (n_main < tiles_n) run_gemm<128, 256, 4, 2, EPI, 64, true>(g, n_main, tiles_n - n_main, 1, st);
     } else {
         run_gemm<128, 128, 2, 2, EPI>(g, 0, (g.N + 127) / 128, 2, st);
+        return false;
     }
+    return true;
 }
 
 // ---------------------------------------------------------------- float32
@@ -842,11 +879,13 @@ void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, voi
     dispatch<EPI_SWIGLU>(g, st);
 }
 
-void launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, int M, int V, int d,
+bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
                              hipStream_t st) {
     GemmArgs g{};
     g.A = (const bf16*)xh; g.W0 = (const bf16*)w; g.M = M; g.N = V; g.K = d; g.Cf = logits;
-    dispatch<EPI_LOGITS>(g, st);
+    g.parts = reinterpret_cast<float2*>(parts);
+    g.n_parts = (V + rowparts::PART - 1) / rowparts::PART;
+    return dispatch<EPI_LOGITS>(g, st) && parts != nullptr;
 }
 
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc, int accumulate,

@@ -59,6 +59,7 @@ struct mulo_ctx {
     float* attn_part;    // partial results of the key-split single-token attention
     int32_t* isl_pos;    // [maxM] island-parallel re-sampling: cache row of every slot of a pass
     uint8_t* isl_hide;   // [maxM] positions hidden from the queries of a pass
+    float* row_parts;    // [maxM, ceil(V / 128)] float pairs: softmax statistics per 128-column part (lm-head epilogue)
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
@@ -72,8 +73,9 @@ namespace {
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+constexpr int N_BUF = 17;
 struct Layout {
-    size_t off[16];
+    size_t off[N_BUF];
     size_t total;
 };
 
@@ -81,13 +83,13 @@ Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
     const size_t e = c.dtype == MULO_BF16 ? 2 : 4;
     const size_t tmpw = c.dtype == MULO_F32 ? (3 * d > 2 * f ? 3 * d : 2 * f) : 0;
-    const size_t sizes[16] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
+    const size_t sizes[N_BUF] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
                               M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
                               c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0,
-                              M * 4, M};
+                              M * 4, M, c.dtype == MULO_BF16 ? M * ((V + 127) / 128) * 8 : 0};
     Layout l{};
     size_t o = 0;
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < N_BUF; ++i) {
         l.off[i] = o;
         o += align_up(sizes[i]);
     }
@@ -155,8 +157,10 @@ struct Scatter {
     int P0, Lblk;
 };
 
-void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_t* tok, const void* emb,
-                     float* logits, const Scatter* sc = nullptr) {
+// want_parts: also leave the softmax statistics of every 128-column part of every logit row in c->row_parts
+// (returns whether the lm-head kernel that ran produces them)
+bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_t* tok, const void* emb,
+                     float* logits, const Scatter* sc = nullptr, bool want_parts = false) {
     const mulo_model_cfg& m = c->cfg;
     const int M = B * L, d = m.d_model, f = m.d_ffn, V = m.vocab, dt = m.dtype;
     const size_t e = c->esz;
@@ -208,8 +212,9 @@ void enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     }
     { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, st); }
     PROF(MULO_PROF_GEMM_LM_HEAD);
-    if (dt == MULO_BF16) launch_gemm_logits_bf16(c->xh, c->w.lm_head, logits, M, V, d, st);
-    else launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);
+    if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, st);
+    launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);
+    return false;
 }
 
 void enqueue_upsample(mulo_ctx* c, int B, int h, int w, int r, const float* draft, int input_is_probs,
@@ -225,8 +230,10 @@ void enqueue_upsample(mulo_ctx* c, int B, int h, int w, int r, const float* draf
     if (q_hi) launch_gather_rows(q_lo, q_row, q_hi, B, h * w, h * r * w * r, V, c->st);
 }
 
-void enqueue_decide(mulo_ctx* c, const DecideArgs& a) {
-    { PROF(MULO_PROF_ACCEPT); launch_accept(a, c->st); }
+void enqueue_decide(mulo_ctx* c, const DecideArgs& a, bool have_parts = false) {
+    { PROF(MULO_PROF_ACCEPT);
+      if (have_parts) launch_accept_from_parts(a, c->row_parts, (a.V + 127) / 128, c->st);
+      else launch_accept(a, c->st); }
     { PROF(MULO_PROF_OTHER); launch_decide_finish(a, c->st); }
     { PROF(MULO_PROF_MASK_SAMPLE); launch_mask_sample(a, c->st); }
 }
@@ -357,6 +364,7 @@ mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* 
     c->attn_part = (float*)(b + l.off[13]);
     c->isl_pos = (int32_t*)(b + l.off[14]);
     c->isl_hide = (uint8_t*)(b + l.off[15]);
+    c->row_parts = c->esz == 2 ? (float*)(b + l.off[16]) : nullptr;
     *out = c;
     return MULO_OK;
 }
@@ -506,13 +514,20 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     hipStream_t st = ctx->st;
     int32_t* thi = tokens_hi ? tokens_hi : ctx->tokens_hi;
     float* lg = logits ? logits : ctx->logits;
-    // Step 2
-    enqueue_upsample(ctx, B, h_blk, w, r, need_q ? draft : nullptr, input_is_probs, draft_tokens, thi, ctx->q_lo,
-                     ctx->q_row, nullptr);
+    // Step 2, the tokens (the draft distributions follow the target pass, see below)
+    enqueue_upsample(ctx, B, h_blk, w, r, nullptr, input_is_probs, draft_tokens, thi, ctx->q_lo, ctx->q_row, nullptr);
     // Step 3: inputs [prev, x~_0 .. x~_{L-2}] so that logit row j is p of draft position j
     { mulo_ctx* c = ctx; PROF(MULO_PROF_OTHER); launch_shift_inputs(prev_tokens, thi, ctx->inputs, B, L, st);
       if (cfg_on) launch_shift_inputs(prev_tokens, thi, ctx->inputs + (int64_t)B * L, B, L, st); }
-    enqueue_forward(ctx, kv, B2, L, P, ctx->inputs, nullptr, lg);
+    // the accept test needs only the softmax statistics of a logit row and the draft token's logit: when it is the
+    // plain test (no pooling, no guidance) the lm-head's epilogue leaves the statistics and the rows are not re-read
+    const bool plain = p->pool_k <= 1 && !cfg_on;
+    const bool have_parts = enqueue_forward(ctx, kv, B2, L, P, ctx->inputs, nullptr, lg, nullptr, plain);
+    // Step 2, the draft distributions q_lo: only the decision stage reads them, and run here they separate the
+    // lm-head's writes of the logits from the re-draw's reads of them (both kernels measured faster in this order)
+    if (need_q) { mulo_ctx* c = ctx; PROF(MULO_PROF_UPSAMPLE);
+        if (input_is_probs) launch_copy_rows(draft, ctx->q_lo, (int64_t)B * n_lo * V, st);
+        else launch_softmax_rows(draft, ctx->q_lo, (int64_t)B * n_lo, V, st); }
     // Steps 4-5 + residual re-draw
     DecideArgs a{};
     fill_decide(a, ctx->cfg.vocab, ctx->rowmax, ctx->rowinv, B, p);
@@ -520,7 +535,7 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     a.logits_u = cfg_on ? lg + (int64_t)B * L * V : nullptr;
     a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = nullptr;
-    enqueue_decide(ctx, a);
+    enqueue_decide(ctx, a, have_parts);
     return check_launch();
 }
 

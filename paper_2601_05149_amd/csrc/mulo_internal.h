@@ -62,6 +62,9 @@ void launch_island_select(const int32_t* prev, const int32_t* tokens, const uint
 void launch_island_draw(const float* logits, const int32_t* pos_tab, int32_t* tokens, float* logits_out, int B,
                         int L, int V, int P, int cap, uint64_t seed, uint64_t rng_counter, hipStream_t st);
 void launch_accept(const DecideArgs& a, hipStream_t st);         // softmax statistics + accept test
+// the accept test from row parts (m, s per 128 columns, float pairs [rows, n_parts]) that the lm-head GEMM left;
+// needs pool_k <= 1, no probability output and no guidance
+void launch_accept_from_parts(const DecideArgs& a, const float* parts, int n_parts, hipStream_t st);
 void launch_decide_finish(const DecideArgs& a, hipStream_t st);  // t0, Eq. 6-7 mask, the step's counters
 void launch_mask_sample(const DecideArgs& a, hipStream_t st);    // residual draw of the marked positions
 void launch_shift_inputs(const int32_t* prev, const int32_t* tokens_hi, int32_t* inputs, int B,
@@ -91,7 +94,10 @@ void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N
                             hipStream_t st);
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f,
                              int d, hipStream_t st);
-void launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, int M, int V, int d,
+// parts: nullptr, or float pairs [M, ceil(V / 128)] that receive the softmax statistics of every 128-column part of
+// every row (row_parts.h); returns whether they were written (only the kernels whose wavefront tile is 128 columns
+// wide produce them)
+bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
                              hipStream_t st);
 size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim);   // partial results of the key split
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
