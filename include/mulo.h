@@ -285,6 +285,13 @@ MULO_API mulo_status mulo_rejection_islands(mulo_ctx *ctx, int32_t B, int32_t W,
  * this is a reading of Sec. 3.4: only settled positions are context.)  One island that covers everything
  * from its first position on gives exactly mulo_resample_sequential.  The cache rows P .. P+L-1 must hold the
  * verification pass over the block.  bf16 models only.
+ * What the cache holds afterwards: row P+v carries the K/V of INPUT v, the token at position v-1.  A pass rewrites
+ * only the rows of the positions it evaluates, so when position u is re-drawn and u+1 is not evaluated after it
+ * (u+1 is unmarked: the right edge of every island row; or it belongs to another island and was drawn earlier), row
+ * P+u+1 keeps the K/V of the draft token that stood at u during verification: later passes attend to that row as
+ * it is, and after the call the rows from the first marked position on do not match `tokens`.  As after
+ * mulo_verify_step, the caller commits the block (one mulo_verify_forward over the final tokens rewrites rows
+ * P .. P+L-1) before the next step; mulo_resample_sequential, by contrast, refreshes every row from u_start on.
  *   n_passes    size of the largest island over the batch, max_islands >= the largest number of islands of a
  *               sequence: both from counts of mulo_rejection_islands (host values; upper bounds are fine);
  *               B * max_islands <= max_batch * max_block

@@ -120,12 +120,13 @@ def resample_islands(decoder, P, tokens, mask, rank, prev_tokens, *, seed=0, rng
     the positions inside an island one after the other in raster order.  Pass r evaluates, in ONE target
     call, the position of rank r of every island that has one, and draws its token from the target model.
 
-    The paper does not spell out the context of such a concurrent evaluation; the reading taken here follows
-    its statement that the accepted tokens are a valid and sufficient context: the query at block position u
+    The paper does not spell out the context of such a concurrent evaluation; the reading taken here (Sec. 3.4:
+    only settled positions are context): the query at block position u
     attends to the prefix and to those earlier block positions that are settled -- accepted ones (their cache
     rows are the verification pass's) and marked ones re-drawn in an earlier pass (rows rewritten then) --
     and to itself; marked positions not yet re-drawn are hidden.  Its input is the current token at u - 1.
-    Its k, v replace cache row P + u.  Draws use the integer inverse CDF of p with the Philox word of the
+    Its k, v replace cache row P + u; no other row is touched, so the row P + u + 1 of an unmarked successor keeps
+    the k, v of the draft token that stood at u during verification (the caller commits the block afterwards).  Draws use the integer inverse CDF of p with the Philox word of the
     sequential stream at (position, batch element), so one island covering everything from its first
     position on is exactly `resample_sequential`.
 
