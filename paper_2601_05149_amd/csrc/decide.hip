@@ -429,6 +429,52 @@ __device__ __forceinline__ void weights4(const float4 z, const float4 qv, float 
     w[2] = (unsigned long long)__fmul_rn(p2, S); w[3] = (unsigned long long)__fmul_rn(p3, S);
 }
 
+// Chunk sums of the integer weights of a row (pass 1 of the draw): chunk c covers the 256 codebook entries
+// [256 c, 256 c + 256) = 64 lanes x 4 entries.  G float4 per lane are requested together (both rows), and their G
+// wavefront sums run side by side, so that neither the memory latency nor the latency of a lane exchange is paid
+// once per chunk.  GUIDED: the logits are z_u + s (z_c - z_u); USE_Q: residual weights max(0, p - q), else p.
+template <int G, bool GUIDED, bool USE_Q>
+__device__ __forceinline__ void chunk_sums(const Guided z, const float4* __restrict__ q4, float m, float inv, int nv4,
+                                           int nchunks, unsigned long long* chunk) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float4* zc4 = reinterpret_cast<const float4*>(z.zc);
+    const float4* zu4 = reinterpret_cast<const float4*>(z.zu);
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int base = 0; base < nv4; base += TPB * G) {
+        float4 zc[G], zu[G], qv[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {       // rows past the end re-read entry 0 and are not counted
+            const int idx = base + g * TPB + tid, ci = idx < nv4 ? idx : 0;
+            zc[g] = zc4[ci];
+            if constexpr (GUIDED) zu[g] = zu4[ci];
+            if constexpr (USE_Q) qv[g] = q4[ci];
+        }
+        unsigned long long sm[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int idx = base + g * TPB + tid;
+            float4 zz = zc[g];
+            if constexpr (GUIDED)
+                zz = make_float4(guide(zz.x, zu[g].x, z.s), guide(zz.y, zu[g].y, z.s), guide(zz.z, zu[g].z, z.s),
+                                 guide(zz.w, zu[g].w, z.s));
+            unsigned long long w[4];
+            weights4(zz, USE_Q ? qv[g] : zero4, m, inv, !USE_Q, w);
+            sm[g] = idx < nv4 ? (w[0] + w[1]) + (w[2] + w[3]) : 0ull;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+            for (int g = 0; g < G; ++g) sm[g] += __shfl_xor(sm[g], o);
+        if (lane == 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int c = (base >> 6) + g * WAVES + wv;
+                if (c < nchunks) chunk[c] = sm[g];
+            }
+        }
+    }
+}
+
 // Integer-CDF draw of one row by one workgroup: W(x) = floor(w(x) 2^40) with w = max(0, p - q) (or p when
 // use_p), T = (word * tot) >> 32, token = first x whose inclusive prefix exceeds T; an empty residual falls
 // back to p.  The token is stored to *out by the lane that finds it.
@@ -439,17 +485,12 @@ __device__ __forceinline__ void cdf_draw(const Guided z, const float4* __restric
     const int nv4 = V >> 2, nchunks = (nv4 + 63) >> 6;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int attempt = 0; attempt < 2; ++attempt) {
-        for (int base = 0; base < nv4; base += TPB) {
-            const int idx = base + tid;
-            unsigned long long s = 0;
-            if (idx < nv4) {
-                unsigned long long w[4];
-                weights4(z.at4(idx), use_p ? zero4 : q4[idx], m, inv, use_p, w);
-                s = (w[0] + w[1]) + (w[2] + w[3]);
-            }
-            s = wave_sum_u64(s);
-            const int c = (base >> 6) + wv;
-            if (lane == 0 && c < nchunks) chunk[c] = s;
+        if (z.zu) {
+            if (use_p) chunk_sums<2, true, false>(z, q4, m, inv, nv4, nchunks, chunk);
+            else chunk_sums<2, true, true>(z, q4, m, inv, nv4, nchunks, chunk);
+        } else {
+            if (use_p) chunk_sums<4, false, false>(z, q4, m, inv, nv4, nchunks, chunk);
+            else chunk_sums<4, false, true>(z, q4, m, inv, nv4, nchunks, chunk);
         }
         if (tid == 0) *s_retry = 0;
         __syncthreads();
@@ -505,7 +546,19 @@ __device__ __forceinline__ void cdf_draw(const Guided z, const float4* __restric
 __global__ __launch_bounds__(TPB) void k_mask_sample(const DecideArgs a) {
     __shared__ unsigned long long chunk[MAX_CHUNKS];
     __shared__ int s_retry;
-    const int64_t row = blockIdx.x;
+    // Which position this workgroup handles.  Workgroup ids go round-robin over the 8 XCDs (each with its own L2).
+    // When the draft rows are shared by r x r children (replication up-sampling), the children of a draft row are
+    // given to consecutive workgroups of ONE XCD, so that the row comes from memory once instead of once per child.
+    int64_t row = blockIdx.x;
+    if (a.up_r > 1) {
+        const int r2 = a.up_r * a.up_r, n_par = a.L / r2;
+        const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
+        const int64_t pseq = (int64_t)(k / r2) * 8 + x;
+        if (pseq >= (int64_t)a.B * n_par) return;      // uniform over the workgroup (the grid is rounded up)
+        const int child = k % r2, bb = pseq / n_par, par = pseq % n_par;
+        const int I = par / a.up_w, J = par % a.up_w, W = a.up_r * a.up_w;
+        row = (int64_t)bb * a.L + (a.up_r * I + child / a.up_r) * W + a.up_r * J + child % a.up_r;
+    }
     const int b = row / a.L, t = row % a.L, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 
     // R_X membership of this position (Eq. 6-7) was decided by k_decide_finish
@@ -769,7 +822,13 @@ void launch_accept_from_parts(const DecideArgs& a, const float* parts, int n_par
 }
 
 void launch_mask_sample(const DecideArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(k_mask_sample, dim3((unsigned)(a.B * a.L)), dim3(TPB), 0, st, a);
+    unsigned blocks = (unsigned)(a.B * a.L);
+    if (a.up_r > 1) {   // whole groups of 8 draft rows (one per XCD), r * r workgroups each
+        const int r2 = a.up_r * a.up_r;
+        const int64_t parents = (int64_t)a.B * (a.L / r2);
+        blocks = (unsigned)(((parents + 7) / 8) * 8 * r2);
+    }
+    hipLaunchKernelGGL(k_mask_sample, dim3(blocks), dim3(TPB), 0, st, a);
 }
 
 }  // namespace mulo

@@ -535,6 +535,7 @@ mulo_status mulo_verify_step(mulo_ctx* ctx, mulo_kv* kv, int32_t B, int32_t P, c
     a.logits_u = cfg_on ? lg + (int64_t)B * L * V : nullptr;
     a.draft_tokens = thi; a.tokens_out = tokens_out; a.accept = accept; a.mask = mask;
     a.t0 = t0; a.stats = stats; a.p_probs = nullptr;
+    if (need_q && r > 1 && L % (r * r) == 0) { a.up_r = r; a.up_w = w; }
     enqueue_decide(ctx, a, have_parts);
     return check_launch();
 }

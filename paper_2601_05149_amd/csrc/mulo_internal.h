@@ -40,6 +40,10 @@ struct DecideArgs {
     float* p_probs;   // [B, L, V] or nullptr
     float* rowmax;    // [B*L] workspace
     float* rowinv;    // [B*L] workspace: 1 / sum exp
+    // Replication geometry of the draft rows (a verification step): position (r I + a) W + r J + c of the block reads
+    // draft row I up_w + J, W = up_r * up_w.  0: unknown (q_row is the caller's).  Only used to place the r * r
+    // children of a draft row on one XCD next to each other, so that the row is fetched into one L2 once.
+    int up_r, up_w;
 };
 void launch_softmax_rows(const float* in, float* out, int64_t rows, int V, hipStream_t st);
 void launch_copy_rows(const float* in, float* out, int64_t n_floats, hipStream_t st);
