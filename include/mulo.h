@@ -316,6 +316,10 @@ MULO_API mulo_status mulo_resample_islands(mulo_ctx *ctx, mulo_kv *kv, int32_t B
  *   MULO_WS_Q         T [B, n_heads, L, head_dim]  rotated queries of the last layer
  *   MULO_WS_ATTN      T [M, d]             attention output of the last layer (input of the out projection)
  *   MULO_WS_FFN       T [M, d_ffn]         silu(gate) * up of the last layer (input of the down projection)
+ * After a bf16 call of at most 64 tokens (M <= 64: single-token steps, island passes) NORMED, ATTN and FFN are not
+ * row-major: such calls keep the token operand of every projection in the order the matrix instruction reads it
+ * (tokens in groups of 16, columns in steps of 32; element (m, k) of a [M, K] operand sits at
+ * ((m / 16) * (K / 32) + k / 32) * 512 + ((k % 32) / 8 * 16 + m % 16) * 8 + k % 8).
  *   dst  device pointer, at least `bytes` bytes
  * Errors: unknown buffer -> MULO_ERR_RANGE; bytes not a multiple of 16 or larger than the buffer (sized for
  * max_batch * max_block tokens) -> MULO_ERR_SHAPE. */

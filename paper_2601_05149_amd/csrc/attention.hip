@@ -34,6 +34,7 @@ struct AttnArgs {
     const bf16* kc;   // [nl, maxB, nh, S, dh]
     const bf16* vc;   // [nl, maxB, nh, dh, S]
     bf16* out;        // [B*L, nh*dh]
+    int frag;         // out is the token operand of a weight-streaming projection: fragment order (frag_index)
     int B, L, P, nh, max_seq, max_batch, layer;
     float scale_log2;  // log2(e) / sqrt(dh)
     int nsplit;        // > 1: the keys are dealt to nsplit workgroups per (sequence, head); one query tile only
@@ -181,6 +182,19 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
     // MFMA row rho of a K block is fed key kperm(rho): bits 2 and 3 swapped
     const int kperm = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
 
+    // Hidden rows (scattered queries): one flag per lane and 64-key tile (lane i: key 64 t + i), requested a tile
+    // ahead and turned into a 64-bit mask by a ballot, instead of a byte load per score behind the score product.
+    static_assert(BQ > 128 || BKV == 64, "a lane holds the hide flag of one key of a 64-key tile");
+    auto hide_flag = [&](int tile) -> uint8_t {
+        const int tpos = tile * BKV + lane - a.P0;
+        const bool in_block = tpos >= 0 && tpos < a.Lblk;
+        const uint8_t f = a.hide[(int64_t)b * a.Lblk + (in_block ? tpos : 0)];
+        return in_block ? f : (uint8_t)0;
+    };
+    unsigned long long hide_cur = 0;
+    if constexpr (BQ <= 128) {
+        if (a.hide && wave_live) hide_cur = __ballot(hide_flag(t_begin) != 0);
+    }
     gload(t_begin);
     sstore(t_begin & 1);
     __syncthreads();
@@ -189,6 +203,10 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
         const int t_next = t + 1 < t_end ? t + 1 : t;   // the last tile is fetched twice: no branch in the body
         if (wave_live && (scattered || kv0 <= P + wave_jmax)) {
             gload(t_next);
+            uint8_t hide_next = 0;
+            if constexpr (BQ <= 128) {
+                if (a.hide) hide_next = hide_flag(t_next);
+            }
             const bf16* k = sK + (t & 1) * BKV * KS;
             const bf16* v = sV + (t & 1) * DH * VS;
             f32x16 s[BKV / 32];
@@ -214,26 +232,21 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
                         s[kb][r] = key <= qpos ? s[kb][r] : -__builtin_huge_valf();
                     }
             }
-            if (BQ <= 128 && a.hide && kv0 + BKV > a.P0) {   // scattered queries: rows of positions that are not settled yet
-                // all flags of the tile are requested first (clamped into the block), then applied: a test per
-                // score would put every load behind the branch of the one before it
-                const uint8_t* hd_row = a.hide + (int64_t)b * a.Lblk;
-                uint8_t hidden[BKV / 32][16];
+            if constexpr (BQ <= 128) {
+                if (a.hide) {   // scattered queries: rows of positions that are not settled yet (the query's own excepted)
+                    if (hide_cur != 0) {   // uniform over the wavefront; bits are set for rows of the block only
 #pragma unroll
-                for (int kb = 0; kb < BKV / 32; ++kb)
+                        for (int kb = 0; kb < BKV / 32; ++kb) {
+                            const uint32_t mine = (uint32_t)(hide_cur >> (kb * 32)) >> (8 * lh);   // this lane's keys: bits 16 (r / 8) + r % 8
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        int t = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7) - a.P0;
-                        t = t < 0 ? 0 : (t < a.Lblk ? t : a.Lblk - 1);
-                        hidden[kb][r] = hd_row[t];
+                            for (int r = 0; r < 16; ++r) {
+                                const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+                                if (((mine >> (16 * (r >> 3) + (r & 7))) & 1u) && key < qpos) s[kb][r] = -__builtin_huge_valf();
+                            }
+                        }
                     }
-#pragma unroll
-                for (int kb = 0; kb < BKV / 32; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = kv0 + kb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
-                        if (key >= a.P0 && key < qpos && hidden[kb][r]) s[kb][r] = -__builtin_huge_valf();
-                    }
+                    hide_cur = __ballot(hide_next != 0);   // requested at the top of the iteration, for tile t_next
+                }
             }
 #pragma unroll
             for (int kb = 0; kb < BKV / 32; ++kb)
@@ -302,7 +315,8 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
     }
     if (jq_raw < a.L) {
         const float inv = 1.0f / l_run;
-        bf16* op = a.out + ((int64_t)b * a.L + jq) * (a.nh * DH) + hd * DH;
+        const int row = b * a.L + jq;
+        bf16* op = a.out + (int64_t)row * (a.nh * DH) + hd * DH;
 #pragma unroll
         for (int i = 0; i < NDB; ++i)
 #pragma unroll
@@ -310,7 +324,8 @@ __global__ __launch_bounds__(NTH, NTH <= 256 ? 2 : 1) void k_attn_bf16(const Att
                 bf16x4 w;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (__bf16)(active ? o[i][g4 * 4 + e] * inv : 0.f);
-                *reinterpret_cast<bf16x4*>(op + i * 32 + g4 * 8 + lh * 4) = w;
+                const int c = i * 32 + g4 * 8 + lh * 4;   // 4 | c: the four channels share a run of 8
+                *reinterpret_cast<bf16x4*>(a.frag ? a.out + frag_index(row, hd * DH + c, a.nh * DH) : op + c) = w;
             }
     }
 }
@@ -375,7 +390,9 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
         num += p[c] * wgt;
         den += p[DH + 1] * wgt;
     }
-    a.out[((int64_t)b * a.L + j) * (a.nh * DH) + hd * DH + c] = __float2bfloat16(den > 0.f ? num / den : 0.f);
+    const int row = b * a.L + j;
+    a.out[a.frag ? frag_index(row, hd * DH + c, a.nh * DH) : (int64_t)row * (a.nh * DH) + hd * DH + c] =
+        __float2bfloat16(den > 0.f ? num / den : 0.f);
 }
 
 template <int DH, int BQ, int BKV, int NTH>
@@ -409,6 +426,7 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = L; a.P = P; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
+    a.frag = streams_weights(B * L) ? 1 : 0;   // the out projection of such a launch streams its weights
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
     // one query per sequence: too few (sequence, head) pairs to fill the chip, so the keys are split as well
     a.nsplit = 1;
@@ -431,6 +449,7 @@ void launch_attention_scattered_bf16(const void* q, const void* k_cache, const v
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = cap; a.P = P0; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
+    a.frag = streams_weights(B * cap) ? 1 : 0;
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
     a.pos_tab = pos_tab; a.hide = hide; a.P0 = P0; a.Lblk = Lblk;
     // the slots of a sequence are the queries of one workgroup (128 per tile), which streams the sequence's rows

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(TPB) void k_embed(const T* __restrict__ embed, cons
 // once with 16-byte loads and kept in registers (d <= 256 * 4 * NV4); NV4 == 0 re-reads it instead.
 template <typename T, int NV4>
 __global__ __launch_bounds__(TPB) void k_rmsnorm(const float* __restrict__ x, const T* __restrict__ gain,
-                                                 T* __restrict__ out, int d, float eps) {
+                                                 T* __restrict__ out, int d, float eps, int frag) {
     __shared__ float red[TPB / 64];
     const int64_t m = blockIdx.x;
     const float* xr = x + m * d;
@@ -65,14 +65,15 @@ __global__ __launch_bounds__(TPB) void k_rmsnorm(const float* __restrict__ x, co
             const int idx = i * TPB + tid;
             if (idx < nv4) {
                 const int c = idx * 4;
-                st(out, m * d + c, v[i].x * sc * ld(gain, c));
-                st(out, m * d + c + 1, v[i].y * sc * ld(gain, c + 1));
-                st(out, m * d + c + 2, v[i].z * sc * ld(gain, c + 2));
-                st(out, m * d + c + 3, v[i].w * sc * ld(gain, c + 3));
+                const int64_t o = frag ? frag_index((int)m, c, d) : m * d + c;   // 4 | c: one run of 8 either way
+                st(out, o, v[i].x * sc * ld(gain, c));
+                st(out, o + 1, v[i].y * sc * ld(gain, c + 1));
+                st(out, o + 2, v[i].z * sc * ld(gain, c + 2));
+                st(out, o + 3, v[i].w * sc * ld(gain, c + 3));
             }
         }
     } else {
-        for (int c = tid; c < d; c += TPB) st(out, m * d + c, xr[c] * sc * ld(gain, c));
+        for (int c = tid; c < d; c += TPB) st(out, frag ? frag_index((int)m, c, d) : m * d + c, xr[c] * sc * ld(gain, c));
     }
 }
 
@@ -124,17 +125,17 @@ void launch_embed(const void* embed, int dtype, const int32_t* tok, const void* 
 }
 
 template <typename T>
-static void rmsnorm_dispatch(const float* x, const T* gain, T* out, int M, int d, float eps, hipStream_t s) {
-    if ((d & 3) == 0 && d <= 1024) hipLaunchKernelGGL((k_rmsnorm<T, 1>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
-    else if ((d & 3) == 0 && d <= 4096) hipLaunchKernelGGL((k_rmsnorm<T, 4>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
-    else if ((d & 3) == 0 && d <= 8192) hipLaunchKernelGGL((k_rmsnorm<T, 8>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
-    else hipLaunchKernelGGL((k_rmsnorm<T, 0>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps);
+static void rmsnorm_dispatch(const float* x, const T* gain, T* out, int M, int d, float eps, int frag, hipStream_t s) {
+    if ((d & 3) == 0 && d <= 1024) hipLaunchKernelGGL((k_rmsnorm<T, 1>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps, frag);
+    else if ((d & 3) == 0 && d <= 4096) hipLaunchKernelGGL((k_rmsnorm<T, 4>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps, frag);
+    else if ((d & 3) == 0 && d <= 8192) hipLaunchKernelGGL((k_rmsnorm<T, 8>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps, frag);
+    else hipLaunchKernelGGL((k_rmsnorm<T, 0>), dim3(M), dim3(TPB), 0, s, x, gain, out, d, eps, frag);
 }
 
-void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps,
+void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps, bool frag,
                     hipStream_t s) {
-    if (dtype == 1) rmsnorm_dispatch(x, (const __hip_bfloat16*)gain, (__hip_bfloat16*)out, M, d, eps, s);
-    else rmsnorm_dispatch(x, (const float*)gain, (float*)out, M, d, eps, s);
+    if (dtype == 1) rmsnorm_dispatch(x, (const __hip_bfloat16*)gain, (__hip_bfloat16*)out, M, d, eps, frag ? 1 : 0, s);
+    else rmsnorm_dispatch(x, (const float*)gain, (float*)out, M, d, eps, 0, s);
 }
 
 void launch_rope_append_f32(const float* qkv, float* q_out, float* k_cache, float* v_cache, int M, int d,

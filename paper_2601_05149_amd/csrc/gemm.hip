@@ -426,18 +426,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
         for (int i = 0; i < LB; ++i)
             *reinterpret_cast<u32x4*>(b + (trow + i * (NT / CPR)) * LDS_STRIDE + kc8) = rb[i];
     };
-    // Fragments of one k-slice, double-buffered in registers.  Inside a 64-deep K-step the k index is dealt so that
-    // lane half lh owns k in [32 lh, 32 lh + 32) and MFMA slice kk takes its kk-th 8 (both operands alike, so the
-    // products are unchanged): the same deal, hence the same summation order, as in the kernels that fetch an
-    // operand straight from memory, where it makes a lane's bytes contiguous.
+    // Fragments of one k-slice, double-buffered in registers.  Inside every 64 consecutive k the index is dealt so
+    // that lane half lh owns k in [32 lh, 32 lh + 32) and MFMA slice kk takes its kk-th 8 (both operands alike, so
+    // the products are unchanged): the same deal, hence the same summation order, as in the kernels that fetch an
+    // operand straight from memory, where it makes a lane's bytes contiguous.  A 128-deep K-step is two such runs of
+    // 64 one after the other, so the depth of a step does not show in the sums either.
     bf16x8 af[2][MB], bfr[2][NB];
     auto lfrag = [&](const bf16* a, const bf16* b, int kk, int slot) {
+        const int ko = (kk >> 2) * 64 + (kk & 3) * 8;
 #pragma unroll
         for (int i = 0; i < MB; ++i)
-            af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + kk * 8);
+            af[slot][i] = *reinterpret_cast<const bf16x8*>(a + i * 32 * LDS_STRIDE + ko);
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-            bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + kk * 8);
+            bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b + j * 32 * LDS_STRIDE + ko);
     };
 
     // Pipeline over the flattened sequence of K-steps of all this workgroup's tiles.  While step s is
@@ -456,7 +458,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     constexpr int KS = BK / 16;                      // k-slices (one MFMA deep) per K-step
     constexpr int NMS = MB * NB, NF = MB + NB;       // MFMAs and fragment reads per k-slice
     constexpr int NL = LA + LB;                      // staging registers per lane
-    static_assert(KS == 4, "the rotated loop is written for 4 k-slices per K-step");
+    static_assert(KS == 4 || KS == 8, "K-steps are one or two runs of 64");
     auto mm = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
@@ -468,16 +470,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     // their way, so no wavefront waits for LDS with an empty MFMA queue.  Slice kk lives in slot kk & 1; on return
     // slot 1 holds the step's last slice, not yet multiplied.
     auto step_rot = [&](int step) {
-        const bf16* a = sA + (step & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * (BK / 2);
-        const bf16* b = sB + (step & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * (BK / 2);
-        lfrag(a, b, 0, 0);
-        mm(1);
-        lfrag(a, b, 1, 1);
-        mm(0);
-        lfrag(a, b, 2, 0);
-        mm(1);
-        lfrag(a, b, 3, 1);
-        mm(0);
+        const bf16* a = sA + (step & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 32;
+        const bf16* b = sB + (step & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 32;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            lfrag(a, b, kk, kk & 1);
+            mm((kk + 1) & 1);
+        }
     };
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     int gs = 0;   // steps done so far: buffer parity
@@ -500,8 +499,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
         // of slice kk; over the MFMAs of the step's slices 1 and 2 every staging register is written to LDS as soon
         // as its load (requested one iteration ago) is there and is at once requested again for step kt + 2.
         for (; kt < nk - 2; ++kt, ++gs) {
-            const bf16* a = sA + (gs & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * (BK / 2);
-            const bf16* b = sB + (gs & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * (BK / 2);
+            const bf16* a = sA + (gs & 1) * BM * LDS_STRIDE + (wm * TM + fra) * LDS_STRIDE + lh * 32;
+            const bf16* b = sB + (gs & 1) * BN * LDS_STRIDE + (wn * TN + frb) * LDS_STRIDE + lh * 32;
             bf16* na = sA + ((gs + 1) & 1) * BM * LDS_STRIDE + trow * LDS_STRIDE + kc8;
             bf16* nb = sB + ((gs + 1) & 1) * BN * LDS_STRIDE + trow * LDS_STRIDE + kc8;
             auto stage = [&](auto ic) {   // staging register i: to LDS (step kt + 1), then requested again (step kt + 2)
@@ -519,20 +518,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
             };
             // The NL write + load pairs are dealt evenly over the first SPAN MFMAs of the iteration; the rest run
             // bare, so the last LDS writes have landed when the wavefront reaches the barrier.
-            constexpr int SPAN = 4 * NMS - NMS / 2;
+            constexpr int SPAN = KS * NMS - NMS / 2;
             auto before = [](int m) constexpr { return m >= SPAN ? NL : m * NL / SPAN; };   // pairs in front of MFMA m
-            auto phase = [&](auto phc, int kk_next, int slot_next, int slot) {
+            static_for<KS>([&](auto phc) {   // phase 0 multiplies the previous step's last slice
                 constexpr int ph = decltype(phc)::value;
-                if (kk_next >= 0) lfrag(a, b, kk_next, slot_next);
+                lfrag(a, b, ph, ph & 1);
                 static_for<before((ph + 1) * NMS) - before(ph * NMS)>(
                     [&](auto ic) { stage(std::integral_constant<int, before(ph * NMS) + decltype(ic)::value>{}); });
-                mm(slot);
-            };
-            phase(std::integral_constant<int, 0>{}, 0, 0, 1);   // previous step's last slice
-            phase(std::integral_constant<int, 1>{}, 1, 1, 0);
-            phase(std::integral_constant<int, 2>{}, 2, 0, 1);
-            phase(std::integral_constant<int, 3>{}, 3, 1, 0);
-            static_for<4>([&](auto phc) {
+                mm((ph + 1) & 1);
+            });
+            static_for<KS>([&](auto phc) {
                 constexpr int ph = decltype(phc)::value;
                 __builtin_amdgcn_sched_group_barrier(0x100, NF, 0);
                 static_for<NMS>([&](auto mc) {
@@ -599,22 +594,28 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 // instruction of a wavefront reads 64 contiguous bytes of each of 16 rows: whole 64-byte sectors (with the 32-row
 // instruction only two lanes share a row, 32 of every 64 bytes fetched per request), and a matrix of N columns
 // gives N / 16 workgroups (256 for the 4096-column projections: one per CU).  The tokens are the instruction's
-// column dimension (columns m >= M are fed zeros), up to four groups of 16; the accumulators come out as
+// column dimension (columns m >= M are fed zeros), up to four groups of 16, and arrive in fragment order (the
+// producing kernels write them so: one contiguous KB per group and step, no lane exchange); the accumulators come out as
 // D[weight row 4 q + i][token l16], q = lane / 16: a lane owns 4 consecutive output columns of one token.  The
 // 8 partial sums are added in a fixed order through LDS and the epilogue runs on pairs of adjacent columns.
 typedef __attribute__((ext_vector_type(4))) float f32x4v;
 template <int EPI, int MT>
 __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;   // weight matrices (accumulator sets) per column
-    constexpr int U = MT <= 2 ? 8 : 4;              // 32-deep k-steps requested together
+    // 32-deep k-steps in flight per wavefront: what 16 requests of 16 bytes per lane allow, at least 4 (measured at
+    // the 7B shape: 16 -> 181 ms, 24 -> 185, 32 -> 186 for a re-sampling run of 21 island passes)
+    constexpr int U = 16 / (NA + MT) < 4 ? 4 : 16 / (NA + MT);
     __shared__ float part[8][NA * MT][4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, q = lane >> 4;
-    // Loads use another lane order than the MFMA: lane 4 r + c fetches chunk c (16 bytes) of row r, so that four
-    // ADJACENT lanes read 64 contiguous bytes (one access of the vector L1; in the MFMA's own order, lane 16 c + r,
-    // adjacent lanes sit in different rows and every lane is an access of its own: the L1 then limits the kernel).
-    // Each fetched register is moved to the MFMA's order by a lane permutation (ds_bpermute: lane 16 c + r takes
-    // the value of lane 4 r + c); which k a slot holds is unchanged, hence so is every sum.
+    // Weight loads use another lane order than the MFMA: lane 4 r + c fetches chunk c (16 bytes) of row r, so that
+    // four ADJACENT lanes read 64 contiguous bytes (one access of the vector L1; in the MFMA's own order, lane
+    // 16 c + r, adjacent lanes sit in different rows and every lane is an access of its own: the L1 then limits the
+    // kernel).  Each fetched register is moved to the MFMA's order by a lane permutation (ds_bpermute: lane 16 c + r
+    // takes the value of lane 4 r + c); which k a slot holds is unchanged, hence so is every sum.  The permutations
+    // occupy the LDS pipe (measured: about half of the kernel's time with one token group when the token operand was
+    // fetched and permuted the same way, 16 of 20 permutations per step with four groups), which is why the token
+    // operand arrives in fragment order and needs none.
     const int lrow = lane >> 2, lchunk = lane & 3;
     const int from_lane = (4 * l16 + q) << 2;   // byte address of the source lane for ds_bpermute
     const int n_blk = blockIdx.x * 16;     // first output column (gate|up: first feed-forward column)
@@ -638,14 +639,12 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
             w[0] = g.W0 + (int64_t)r * g.K;
         }
     }
-    // token row(s) this lane fetches (rows past M: token 0's row) and whether the token it feeds to the MFMA exists
-    const bf16* xp[MT];
+    // The token operand is stored in fragment order: the KB of (token group t, step s) is contiguous and lane l owns
+    // its bytes [16 l, 16 l + 16) in the MFMA's own order.  Tokens past M are not written by anybody: fed as zeros.
+    const bf16* const xg = g.A + lane * 8;
     bool has_x[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        has_x[t] = t * 16 + l16 < g.M;
-        xp[t] = g.A + (int64_t)(t * 16 + lrow < g.M ? t * 16 + lrow : 0) * g.K + lchunk * 8;
-    }
+    for (int t = 0; t < MT; ++t) has_x[t] = t * 16 + l16 < g.M;
 #pragma unroll
     for (int i = 0; i < NA; ++i) w[i] += lchunk * 8;
     auto to_mfma_order = [&](u32x4 v) {
@@ -663,97 +662,116 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[i][t] = f32x4v{0.f, 0.f, 0.f, 0.f};
     const u32x4 zero = {0u, 0u, 0u, 0u};
-    // U steps at a time, free of branches (steps past the end of the slice re-read the last step and are
-    // multiplied by zeros), so that all their loads are in flight before the first MFMA waits
-    for (int sb = s0; sb < s1; sb += U) {
-        u32x4 wv[NA][U], xv[MT][U];
+    // U steps in flight per wavefront, all the time: the registers of a step are requested again, for the step U
+    // further on, as soon as the step has been multiplied, so the memory pipeline never drains between batches
+    // (a batch that is requested, waited for and multiplied as a whole leaves it empty for a memory round trip
+    // per batch).  Free of lane-dependent branches: steps past the end of the slice re-read the matrix's last
+    // step and are multiplied by zeros.  The last batch requests nothing.
+    u32x4 wv[NA][U], xv[MT][U];
+    auto request = [&](int u, int s) {
+        const int sc = s < steps ? s : steps - 1;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int sc = sb + u < steps ? sb + u : steps - 1;
+        for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * 32);
 #pragma unroll
-            for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * 32);
+        for (int t = 0; t < MT; ++t) xv[t][u] = *reinterpret_cast<const u32x4*>(xg + ((int64_t)t * steps + sc) * 512);
+    };
+    auto permute = [&](int u, int s, bf16x8 (&wf)[NA], bf16x8 (&xf)[MT]) {
+        const bool in_slice = s < s1;
 #pragma unroll
-            for (int t = 0; t < MT; ++t) xv[t][u] = *reinterpret_cast<const u32x4*>(xp[t] + sc * 32);
-        }
+        for (int i = 0; i < NA; ++i) wf[i] = __builtin_bit_cast(bf16x8, to_mfma_order(wv[i][u]));
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool in_slice = sb + u < s1;
-            bf16x8 wf[NA];
-#pragma unroll
-            for (int i = 0; i < NA; ++i) wf[i] = __builtin_bit_cast(bf16x8, to_mfma_order(wv[i][u]));
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const u32x4 xm = to_mfma_order(xv[t][u]);   // every lane takes part: not under the lane-dependent select
-                const bf16x8 xf = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xm : zero);
-#pragma unroll
-                for (int i = 0; i < NA; ++i)
-                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf, acc[i][t], 0, 0, 0);
-            }
-        }
-    }
-    // reduce the K-slices in a fixed order; thread (pr, t, lane) of the first 2 * MT wavefronts then owns
-    // accumulators 2 pr, 2 pr + 1 of token group t = two adjacent columns of token t * 16 + l16
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
+        for (int t = 0; t < MT; ++t) xf[t] = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xv[t][u] : zero);
+    };
+    auto multiply = [&](const bf16x8 (&wf)[NA], const bf16x8 (&xf)[MT]) {
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) part[wave][i * MT + t][r][lane] = acc[i][t][r];
-    __syncthreads();
-    if (wave >= 2 * MT) return;
-    const int pr = wave & 1, tg = wave >> 1;
-    float v0[2], v1[2] = {0.f, 0.f};
+            for (int i = 0; i < NA; ++i)
+                acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[t], acc[i][t], 0, 0, 0);
+    };
+    if (s0 < s1) {   // uniform over the wavefront
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        float sum0 = 0.f, sum1 = 0.f;
+        for (int u = 0; u < U; ++u) request(u, s0 + u);
+        int sb = s0;
+        for (; sb + U < s1; sb += U) {
 #pragma unroll
-        for (int ww = 0; ww < 8; ++ww) {
-            sum0 += part[ww][tg][2 * pr + e][lane];
-            if constexpr (EPI == EPI_SWIGLU) sum1 += part[ww][MT + tg][2 * pr + e][lane];
+            for (int u = 0; u < U; ++u) {
+                bf16x8 wf[NA], xf[MT];
+                permute(u, sb + u, wf, xf);
+                request(u, sb + U + u);
+                multiply(wf, xf);
+            }
         }
-        v0[e] = sum0;
-        v1[e] = sum1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            bf16x8 wf[NA], xf[MT];
+            permute(u, sb + u, wf, xf);
+            multiply(wf, xf);
+        }
     }
+    // reduce the K-slices in a fixed order through LDS; thread (pr, t, lane) of the first 2 * MT wavefronts then
+    // owns accumulators 2 pr, 2 pr + 1 of token group t = two adjacent columns of token t * 16 + l16
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[wave][a * MT + t][r][lane] = acc[a][t][r];
+    __syncthreads();
+    const int pr = wave & 1, tg = wave >> 1;
     const int m = tg * 16 + l16;
-    if (m >= g.M) return;
-    const int n = n_blk + 4 * q + 2 * pr;
-    if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
-        float* dst = g.Cf + (int64_t)m * g.N + n;
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-            if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v0[e] : v0[e];
-    } else if constexpr (EPI == EPI_SWIGLU) {
-        const int f = g.N / 2;
-        bf16* dst = g.Cb + (int64_t)m * f + n;
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-            if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
-    } else if (EPI == EPI_QK || (EPI == EPI_QKV && n < 2 * g.d)) {
-        const int seg = n / g.d, c = n - seg * g.d;
-        const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
-        const TokPlace pl = place(g.ra, m);
-        if (pl.pos < 0) return;
-        const int pos = pl.pos;
-        const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
-        bf16* dst;
-        if (seg == 0) {
-            dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
-        } else {
-            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
-            dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
-        }
-        dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
-        dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
-    } else {   // V: transposed cache
-        const int dh = g.ra.head_dim;
-        const int nv = EPI == EPI_QKV ? n - 2 * g.d : n, nlim = EPI == EPI_QKV ? g.d : g.N;
-        const TokPlace pl = place(g.ra, m);
-        if (pl.pos < 0) return;
+    if (wave >= 2 * MT || m >= g.M) return;
+    {
+        float v0[2], v1[2] = {0.f, 0.f};
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int hd = (nv + e) / dh, cc = (nv + e) % dh;
-            const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
-            if (nv + e < nlim) g.vc[(hb * dh + cc) * g.ra.max_seq + pl.pos] = __float2bfloat16(v0[e]);
+            float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < 8; ++ww) {
+                sum0 += part[ww][tg][2 * pr + e][lane];
+                if constexpr (EPI == EPI_SWIGLU) sum1 += part[ww][MT + tg][2 * pr + e][lane];
+            }
+            v0[e] = sum0;
+            v1[e] = sum1;
+        }
+        const int n = n_blk + 4 * q + 2 * pr;
+        if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
+            float* dst = g.Cf + (int64_t)m * g.N + n;
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v0[e] : v0[e];
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            const int f = g.N / 2;
+            bf16* dst = g.Cb + frag_index(m, n, f);   // the down projection streams too: its token operand, fragment order
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
+        } else {
+            const TokPlace pl = place(g.ra, m);
+            if (pl.pos < 0) return;   // an unused slot of a scattered launch
+            const int dh = g.ra.head_dim, pos = pl.pos;
+            if (EPI == EPI_QK || (EPI == EPI_QKV && n < 2 * g.d)) {
+                const int seg = n / g.d, c = n - seg * g.d;
+                const int hd = c / dh, cc = c % dh;
+                const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
+                bf16* dst;
+                if (seg == 0) {
+                    dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
+                } else {
+                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                    dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
+                }
+                dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
+                dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
+            } else {   // V: transposed cache
+                const int nv = EPI == EPI_QKV ? n - 2 * g.d : n, nlim = EPI == EPI_QKV ? g.d : g.N;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int hd = (nv + e) / dh, cc = (nv + e) % dh;
+                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                    if (nv + e < nlim) g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = __float2bfloat16(v0[e]);
+                }
+            }
         }
     }
 }
@@ -771,7 +789,7 @@ void run_gemv(const GemmArgs& g, hipStream_t st) {
 // returns whether the launch ran on the kernels whose wavefront tile is 128 columns wide (whole tiles)
 template <int EPI>
 bool dispatch(const GemmArgs& g, hipStream_t st) {
-    if (g.M <= 64 && (EPI != EPI_QK || g.d % 32 == 0)) {   // a handful of tokens: stream the weights
+    if (streams_weights(g.M)) {   // a handful of tokens: stream the weights (A is in fragment order)
         run_gemv<EPI>(g, st);
         return false;
     }
@@ -800,7 +818,12 @@ bool dispatch(const GemmArgs& g, hipStream_t st) {
         run_gemm<256, 256, 4, 2, EPI, 64, true>(g, 0, n_main, 1, st);
         if (n_main < tiles_n) run_gemm<128, 256, 4, 2, EPI, 64, true>(g, n_main, tiles_n - n_main, 1, st);
     } else {
-        run_gemm<128, 128, 2, 2, EPI>(g, 0, (g.N + 127) / 128, 2, st);
+        // One round of tiles (a few hundred tokens: the paper's batch-1 setting) leaves one workgroup per CU, and a
+        // K-step then costs its fixed chain of latencies whatever its depth: 128-deep steps halve their number
+        // (out and down projections at 576 tokens: +16 %).  The sums are the same bits (see the k deal above).
+        const int64_t small_tiles = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+        if (g.K % 128 == 0 && g.K >= 256 && small_tiles <= cus64) run_gemm<128, 128, 2, 2, EPI, 128>(g, 0, (g.N + 127) / 128, 1, st);
+        else run_gemm<128, 128, 2, 2, EPI>(g, 0, (g.N + 127) / 128, 2, st);
         return false;
     }
     return true;
@@ -854,7 +877,7 @@ void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const 
     GemmArgs g{};
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk;
     g.M = M; g.N = 2 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.d = d; g.ra = ra;
-    if (M <= 64 && d % 32 == 0) {   // a handful of tokens: q | k | v stream through one launch
+    if (streams_weights(M)) {   // a handful of tokens: q | k | v stream through one launch (xh is in fragment order)
         g.W2 = (const bf16*)wv; g.vc = (bf16*)v_cache; g.N = 3 * d;
         run_gemv<EPI_QKV>(g, st);
         return;

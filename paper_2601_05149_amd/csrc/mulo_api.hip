@@ -81,9 +81,10 @@ struct Layout {
 
 Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
+    const size_t M16 = (M + 15) / 16 * 16;   // the operands of the projections hold whole groups of 16 tokens (fragment order)
     const size_t e = c.dtype == MULO_BF16 ? 2 : 4;
     const size_t tmpw = c.dtype == MULO_F32 ? (3 * d > 2 * f ? 3 * d : 2 * f) : 0;
-    const size_t sizes[N_BUF] = {M * d * 4, M * d * e, M * d * e, M * d * e, M * f * e, M * tmpw * 4,
+    const size_t sizes[N_BUF] = {M * d * 4, M16 * d * e, M * d * e, M16 * d * e, M16 * f * e, M * tmpw * 4,
                               M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
                               c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0,
                               M * 4, M, c.dtype == MULO_BF16 ? M * ((V + 127) / 128) * 8 : 0};
@@ -165,6 +166,8 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     const int M = B * L, d = m.d_model, f = m.d_ffn, V = m.vocab, dt = m.dtype;
     const size_t e = c->esz;
     hipStream_t st = c->st;
+    // a handful of tokens: every bf16 projection streams its weights and takes its token operand in fragment order
+    const bool frag = dt == MULO_BF16 && streams_weights(M);
     { PROF(MULO_PROF_NORM_EMBED); launch_embed(c->w.embed, dt, tok, emb, c->x, M, d, V, st); }
     for (int l = 0; l < m.n_layers; ++l) {
         RopeArgs ra{c->w.rope_cos, c->w.rope_sin, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l};
@@ -178,7 +181,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
         const char* wd = (const char*)c->w.w_down + (size_t)l * d * f * e;
         const char* g_attn = (const char*)c->w.attn_norm + (size_t)l * d * e;
         const char* g_ffn = (const char*)c->w.ffn_norm + (size_t)l * d * e;
-        { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_attn, dt, c->xh, M, d, m.rms_eps, st); }
+        { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_attn, dt, c->xh, M, d, m.rms_eps, frag, st); }
         if (dt == MULO_BF16) {
             { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
             { PROF(MULO_PROF_ATTENTION);
@@ -187,7 +190,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
               else launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim,
                                          m.max_seq, m.max_batch, l, st); }
             { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }
-            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
+            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, frag, st); }
             { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, st); }
             { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, st); }
         } else {
@@ -202,7 +205,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
               launch_attention_f32((const float*)c->qbuf, (const float*)kv->k, (const float*)kv->v, (float*)c->att,
                                    nullptr, B, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st); }
             { PROF(MULO_PROF_GEMM_OUT); launch_gemm_f32((const float*)c->att, (const float*)wo, c->x, M, d, d, d, 1, st); }
-            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, st); }
+            { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, frag, st); }
             { PROF(MULO_PROF_GEMM_GATE_UP);
               launch_gemm_f32(xh, (const float*)wg, c->tmp, M, f, d, 2 * f, 0, st);
               launch_gemm_f32(xh, (const float*)wu, c->tmp + f, M, f, d, 2 * f, 0, st); }
@@ -210,7 +213,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
             { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_f32((const float*)c->hmid, (const float*)wd, c->x, M, d, f, d, 1, st); }
         }
     }
-    { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, st); }
+    { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, frag, st); }
     PROF(MULO_PROF_GEMM_LM_HEAD);
     if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, st);
     launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);

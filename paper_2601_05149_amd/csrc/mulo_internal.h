@@ -14,6 +14,19 @@ void note_hip_error(hipError_t e);
 // false, with the error noted, when the runtime refuses.
 bool ensure_dynamic_lds(const void* kern, int bytes, int* state);
 
+// Launches of at most STREAM_MAX_TOKENS tokens (single-token decoding of a few sequences, island passes) run every
+// bf16 projection in the weight-streaming kernel.  That kernel feeds its MFMA straight from registers, so its token
+// operand [M, K] is kept in the order the instruction reads it (FRAGMENT ORDER): tokens in groups of 16, k in steps of
+// 32; the 1 KB of (group t, step s) is contiguous, and inside it lane 16 c + r of a wavefront owns 16 bytes: k
+// 32 s + 8 c .. + 7 of token 16 t + r.  The kernels that produce such an operand (RMSNorm, attention, the SwiGLU
+// epilogue) write it in this order when the launch streams; one load instruction then reads a whole contiguous KB
+// and no lane exchange is needed.  Buffers are sized for whole groups of 16 tokens.
+constexpr int STREAM_MAX_TOKENS = 64;
+inline bool streams_weights(int M) { return M <= STREAM_MAX_TOKENS; }
+__host__ __device__ inline int64_t frag_index(int m, int k, int K) {   // in elements; runs of 8 k stay contiguous
+    return ((int64_t)(m >> 4) * (K >> 5) + (k >> 5)) * 512 + (((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7);
+}
+
 // ---- decision stage (decide.hip) -------------------------------------------
 struct DecideArgs {
     int B, L, V;
@@ -87,7 +100,8 @@ struct RopeArgs {
 // x[m, :] = embed[clamp(tok[m])]  (float32 residual stream); T = float or bf16 storage
 void launch_embed(const void* embed, int dtype, const int32_t* tok, const void* in_embeds, float* x,
                   int M, int d, int V, hipStream_t st);
-void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps,
+// frag: write `out` in fragment order (bf16 launches that stream the weights)
+void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int M, int d, float eps, bool frag,
                     hipStream_t st);
 
 // bf16 MFMA GEMMs, C = A[M,K] * W[N,K]^T with fused epilogues
