@@ -668,12 +668,17 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     // per batch).  Free of lane-dependent branches: steps past the end of the slice re-read the matrix's last
     // step and are multiplied by zeros.  The last batch requests nothing.
     u32x4 wv[NA][U], xv[MT][U];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < U; ++u) xv[t][u] = zero;
     auto request = [&](int u, int s) {
         const int sc = s < steps ? s : steps - 1;
 #pragma unroll
         for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * 32);
 #pragma unroll
-        for (int t = 0; t < MT; ++t) xv[t][u] = *reinterpret_cast<const u32x4*>(xg + ((int64_t)t * steps + sc) * 512);
+        for (int t = 0; t < MT; ++t)   // lanes whose token does not exist request nothing (a 4-token launch reads 4 x 64 bytes of the KB)
+            if (has_x[t]) xv[t][u] = *reinterpret_cast<const u32x4*>(xg + ((int64_t)t * steps + sc) * 512);
     };
     auto permute = [&](int u, int s, bf16x8 (&wf)[NA], bf16x8 (&xf)[MT]) {
         const bool in_slice = s < s1;
