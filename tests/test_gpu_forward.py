@@ -256,3 +256,46 @@ def test_forward_single_token_steps_with_split_keys(dh, nh):
         t = G.uniform_tokens((B, 1), m["vocab"], 5, tag=10 + step)
         check_bf16_logits("single token, %d cached rows, dh %d" % (Pn + step, dh), gpu_forward(ctx, kv, t, Pn + step),
                           dr.forward(t, Pn + step).numpy(), du.forward(t, Pn + step).numpy(), strict=True)
+
+
+def frag_to_rows(buf, M, K):
+    """Undo the fragment order of a [M, K] token operand (include/mulo.h, mulo_workspace_read): element (m, k)
+    sits at ((m / 16) * (K / 32) + k / 32) * 512 + ((k % 32) / 8 * 16 + m % 16) * 8 + k % 8."""
+    m = np.arange(M)[:, None]
+    k = np.arange(K)[None, :]
+    idx = ((m // 16) * (K // 32) + k // 32) * 512 + ((k % 32) // 8 * 16 + m % 16) * 8 + k % 8
+    return buf.reshape(-1)[idx]
+
+
+@pytest.mark.parametrize("B,L", [(3, 1), (4, 13), (2, 32)])
+def test_forward_few_tokens_keeps_its_operands_in_fragment_order(B, L):
+    """Launches of at most 64 tokens (one, four and four token groups of 16; 3, 52 and 64 tokens) run every projection
+    in the weight-streaming kernel, whose token operand the producing kernels leave in the matrix instruction's own
+    order.  One layer: the attention output and silu(gate) * up read back through mulo_workspace_read, put back in
+    row order by the documented formula, are the oracle's stage tensors; the logits are held to the usual bound."""
+    m = dict(n_layers=1, d_model=256, n_heads=2, head_dim=128, d_ffn=512, vocab=1024, dtype="bf16", rms_eps=1e-5)
+    Pn, S, M = 70, 112, B * L
+    w = G.make_weights(m, seed=11)
+    ctx, cos, sin = make_ctx(m, w, B, S, 72)
+    kv = mulo.alloc_kv(ctx, DEV)
+    dr, du = pair(m, w, cos, sin, B, S)
+    pre = G.uniform_tokens((B, Pn), m["vocab"], 11, tag=0)
+    gpu_forward(ctx, kv, pre, 0)
+    dr.forward(pre, 0)
+    du.forward(pre, 0)
+    blk = G.uniform_tokens((B, L), m["vocab"], 11, tag=1)
+    stages = {}
+    z_r = dr.forward(blk, Pn, stages=stages).numpy()
+    z = gpu_forward(ctx, kv, blk, Pn)
+    check_bf16_logits("%d x %d tokens, weight-streaming projections" % (B, L), z, z_r, du.forward(blk, Pn).numpy(), strict=True)
+    M16 = (M + 15) // 16 * 16
+    for name, which, K in (("att", mulo.MULO_WS_ATTN, m["d_model"]), ("hmid", mulo.MULO_WS_FFN, m["d_ffn"])):
+        buf = torch.empty(M16 * K, dtype=torch.bfloat16, device=DEV)
+        mulo.mulo_workspace_read(ctx, which, buf)
+        torch.cuda.synchronize()
+        got = frag_to_rows(buf.float().cpu().numpy(), M, K)
+        want = stages[name][0].reshape(M, K).double().numpy()
+        err = np.abs(got - want)
+        tol = 2.0 ** -5 * (np.abs(want) + np.sqrt((want ** 2).mean()))
+        say("  %s in fragment order, %d tokens: max|err| %.3g, beyond tolerance %d of %d" % (name, M, err.max(), (err > tol).sum(), err.size))
+        assert (err > tol).mean() <= 0.005 and err.max() <= 0.25 * np.abs(want).max()
