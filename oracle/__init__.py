@@ -24,10 +24,8 @@ Pin status (see tests/test_oracle_*.py):
   decoder : structure pinned (causality, textbook special cases, float64
       triple-loop pieces); the logit VALUES for random weights have no external
       reference -> "parity unpinned" for the values themselves.
-  philox  : uniformity / independence pinned statistically; its identity as
-      Philox4x32-10 has no known-answer vector available here -> the constants
-      are "parity unpinned" (any good counter-based generator satisfies the
-      method, which fixes none).
+  philox  : pinned: the three published known-answer vectors of Philox4x32-10 (tests/golden/), and
+      uniformity / independence / avalanche statistically.
   step.resample_islands : pinned as far as the paper fixes it (one island from t0 on = sequential
       re-sampling, itself pinned as ancestral sampling; one target call per rank; draws are inverse-CDF
       draws of the rows produced; stale cache rows of pending positions never reach a result).  WHICH

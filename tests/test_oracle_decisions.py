@@ -18,6 +18,24 @@ from oracle import upsample as UP
 
 
 # ------------------------------------------------------------------ uniforms
+def test_philox_is_philox4x32_10_by_its_published_known_answers():
+    """The generator's identity: the three known-answer vectors published with the reference implementation of
+    Salmon et al. (SC'11) for philox4x32 with 10 rounds (tests/golden/philox4x32_10_known_answers.txt).  A wrong
+    multiplier, Weyl constant, round count or output-word order fails all 12 words."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_known_answers.txt")
+    rows = [[int(x, 16) for x in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        out = PH.philox4x32(r[0], r[1], r[2], r[3], r[4], r[5])
+        assert [int(o) for o in out] == r[6:10]
+    # the vectorised path gives the same words as the scalar one
+    c = np.array([r[:4] for r in rows], dtype=np.uint64)
+    for i, r in enumerate(rows):
+        out = PH.philox4x32(c[:, 0], c[:, 1], c[:, 2], c[:, 3], r[4], r[5])
+        assert [int(o[i]) for o in out] == r[6:10]
+
+
 def test_philox_zero_rounds_is_identity_and_rounds_matter():
     c = [np.arange(5), np.arange(5) + 7, 3, 9]
     out0 = PH.philox4x32(*c, 11, 22, rounds=0)
