@@ -309,6 +309,10 @@ def main():
                          "roofline kernel there, every class in two extra un-timed steps")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the secondary points (cfg4 last and first block) that the default run adds")
+    ap.add_argument("--constant-weights", type=float, default=None, metavar="C",
+                    help="diagnostic, never the reported workload: every weight matrix is filled with C, so the operands "
+                         "of the matrix instructions stop changing from one to the next; the same kernels then show what "
+                         "they sustain when the chip does not lower its clock with the switching activity of the data")
     ap.add_argument("--resample", type=float, default=None, metavar="RATE",
                     help="instead of the verify step: time the re-sampling of the workload's last block after a "
                          "synthetic verification with this fraction of rejected positions (radius 1) - "
@@ -345,6 +349,10 @@ def main():
     w = G.make_weights(m, seed=c["seed"])
     cos, sin = G.rope_table(WC.get("cfg5_L1024")["max_seq"] if c["model_name"] == "7b" else c["max_seq"], m["head_dim"])
     wd = {k: v.to(dev) for k, v in w.items()}
+    if a.constant_weights is not None:
+        for name, t in wd.items():
+            if t.dim() >= 2 and "norm" not in name:
+                t.fill_(a.constant_weights)
     rope = (torch.tensor(cos[:c["max_seq"]], device=dev), torch.tensor(sin[:c["max_seq"]], device=dev))
 
     if a.resample is not None:
@@ -357,7 +365,8 @@ def main():
     res = {"metric": "verified image tokens/sec (1 GPU) per verify step", "value": main_res.pop("value"),
            "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
            "ms_per_step": main_res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": m["dtype"], "data": "synthetic"}
+           "dtype": m["dtype"],
+           "data": "synthetic" if a.constant_weights is None else "synthetic, CONSTANT weights (clock diagnostic, not the workload)"}
     res.update(main_res)
     # secondary points, outside the timed region of the headline: the batch-4 1024-token workload at its last block
     # (the largest cache) and at its first block (P = the prefix only) for contrast
