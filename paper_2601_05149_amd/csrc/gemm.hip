@@ -665,8 +665,9 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     // U steps in flight per wavefront, all the time: the registers of a step are requested again, for the step U
     // further on, as soon as the step has been multiplied, so the memory pipeline never drains between batches
     // (a batch that is requested, waited for and multiplied as a whole leaves it empty for a memory round trip
-    // per batch).  Free of lane-dependent branches: steps past the end of the slice re-read the matrix's last
-    // step and are multiplied by zeros.  The last batch requests nothing.
+    // per batch).  No branch on the step index: steps past the end of the slice re-read the matrix's last step and
+    // are multiplied by zeros (a branch there makes the compiler wait for every load in flight).  The last batch
+    // requests nothing.
     u32x4 wv[NA][U], xv[MT][U];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
