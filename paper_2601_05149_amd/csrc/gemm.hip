@@ -31,7 +31,7 @@ typedef __hip_bfloat16 bf16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 enum { EPI_QK = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3, EPI_V = 4,
-       EPI_QKV = 5 };   // q | k | v in one launch: weight-streaming kernel only
+       EPI_QKV = 5 };   // q | k | v in one launch: the weight-streaming kernel, and tiled launches of a few hundred tokens
 
 struct GemmArgs {
     const bf16* A;        // [M, K]
@@ -71,7 +71,7 @@ __device__ __forceinline__ float silu(float g) { return g * __builtin_amdgcn_rcp
 template <int EPI, int BN, int TN>
 __device__ __forceinline__ int b_row_src(const GemmArgs& g, int n0, int tile_n, int nl, int& which) {
     int r;
-    if constexpr (EPI == EPI_QK) {
+    if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
         const int seg = n0 / g.d;
         which = seg;
         r = n0 - seg * g.d + nl;
@@ -94,7 +94,7 @@ template <int EPI, int BN, int TN>
 __device__ __forceinline__ const bf16* b_row(const GemmArgs& g, int n0, int tile_n, int nl) {
     int which;
     const int r = b_row_src<EPI, BN, TN>(g, n0, tile_n, nl, which);
-    return (which ? g.W1 : g.W0) + (int64_t)r * g.K;
+    return (which == 0 ? g.W0 : which == 1 ? g.W1 : g.W2) + (int64_t)r * g.K;
 }
 
 // Whole-tile launches address their operands through buffer descriptors: the descriptor (matrix base and size)
@@ -110,7 +110,7 @@ __device__ __forceinline__ u32x4 bload(rsrc_t r, uint32_t lane_off, uint32_t bas
 // rows of the weight matrices of each fused problem
 template <int EPI>
 __device__ __forceinline__ int64_t weight_rows(const GemmArgs& g) {
-    return EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N;
+    return (EPI == EPI_QK || EPI == EPI_QKV) ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N;
 }
 
 // Which tile row feeds MFMA row rho: bits 2 and 3 exchanged.  With it, accumulator r of a lane
@@ -292,7 +292,18 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[MB][NB
                             const int n = n0 + wn * TN + cl, seg = n / g.d, c = n - seg * g.d;
                             const int dh = g.ra.head_dim, hd = c / dh, cc = c % dh;
                             const TokPlace pl = place(g.ra, m);
-                            if (pl.pos >= 0) {
+                            if (EPI == EPI_QKV && seg == 2) {
+                                // V with the operands exchanged: a lane holds 8 consecutive channels of ONE token, the
+                                // 32 lanes of a half are 32 consecutive tokens = 64 contiguous bytes of a row of the
+                                // transposed cache per store (fine for a few hundred tokens; the large launches keep the
+                                // V projection of its own, whose lanes hold 8 consecutive tokens)
+                                if (pl.pos >= 0) {
+                                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+#pragma unroll
+                                    for (int e = 0; e < 8; ++e)
+                                        g.vc[(hb * dh + cc + e) * g.ra.max_seq + pl.pos] = __float2bfloat16(v[e]);
+                                }
+                            } else if (pl.pos >= 0) {
                                 const int pos = pl.pos;
                                 const f32x4 cs = *reinterpret_cast<const f32x4*>(g.ra.cos + (int64_t)pos * (dh / 2) + (cc >> 1));
                                 const f32x4 sn = *reinterpret_cast<const f32x4*>(g.ra.sin + (int64_t)pos * (dh / 2) + (cc >> 1));
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
     const uint32_t voff = (uint32_t)(trow * g.K + kc8) * 2u;
     const rsrc_t rA = make_rsrc(g.A, (int64_t)g.M * g.K * 2);
     rsrc_t rW[2] = {make_rsrc(g.W0, weight_rows<EPI>(g) * g.K * 2),
-                    make_rsrc(EPI == EPI_QK || EPI == EPI_SWIGLU ? g.W1 : g.W0, weight_rows<EPI>(g) * g.K * 2)};
+                    make_rsrc(EPI == EPI_QK || EPI == EPI_QKV || EPI == EPI_SWIGLU ? g.W1 : g.W0, weight_rows<EPI>(g) * g.K * 2)};
     // which descriptor pass i of the weight tile reads: gate | up alternate inside a tile (compile-time), q | k is per tile
     auto wsel = [&](int i) -> rsrc_t { return rW[EPI == EPI_SWIGLU ? ((i * RP) % TN >= TN / 2 ? 1 : 0) : 0]; };
     auto setup = [&](int local) {   // operand rows of the chunk's tile `local` (fixed over its K loop)
@@ -386,7 +397,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, (WGM * WGN >= 8 || BM * BN >= 65536)
             for (int i = 0; i < LB; ++i) {
                 int which;
                 sb[i] = (uint32_t)(b_row_src<EPI, BN, TN>(g, n0, tile_n, i * RP, which) * g.K) * 2u;
-                if constexpr (EPI == EPI_QK) { if (i == 0) rW[0] = make_rsrc(which ? g.W1 : g.W0, weight_rows<EPI>(g) * g.K * 2); }
+                if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
+                    if (i == 0) rW[0] = make_rsrc(which == 0 ? g.W0 : which == 1 ? g.W1 : g.W2, weight_rows<EPI>(g) * g.K * 2);
+                }
             }
         } else {
 #pragma unroll
@@ -793,24 +806,35 @@ void run_gemv(const GemmArgs& g, hipStream_t st) {
 }
 
 // returns whether the launch ran on the kernels whose wavefront tile is 128 columns wide (whole tiles)
+enum { CLS_STREAM, CLS_BIG, CLS_MID, CLS_SMALL };
 template <int EPI>
-bool dispatch(const GemmArgs& g, hipStream_t st) {
-    if (streams_weights(g.M)) {   // a handful of tokens: stream the weights (A is in fragment order)
-        run_gemv<EPI>(g, st);
-        return false;
-    }
+int classify(const GemmArgs& g) {
+    if (streams_weights(g.M)) return CLS_STREAM;   // a handful of tokens: stream the weights (A is in fragment order)
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
-    // (whole tiles only: their operand rows are addressed from scalar bases; a Q|K tile must not straddle the two weights)
-    const bool whole_n = g.N % 256 == 0 && (EPI == EPI_QK ? g.d % 256 == 0 : true) &&
+    // (whole tiles only: their operand rows are addressed from scalar bases; a q|k|v tile must not straddle two weights)
+    const bool whole_n = g.N % 256 == 0 && ((EPI == EPI_QK || EPI == EPI_QKV) ? g.d % 256 == 0 : true) &&
                          (int64_t)g.K * 256 * 2 < (1ll << 31) && (int64_t)g.M * g.K * 2 < (1ll << 31) &&
-                         (int64_t)(EPI == EPI_QK ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N) * g.K * 2 < (1ll << 31);
+                         (int64_t)((EPI == EPI_QK || EPI == EPI_QKV) ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N) * g.K * 2 < (1ll << 31);
     const bool big = whole_n && g.M >= 1024 && g.M % 256 == 0 &&
                      (int64_t)(g.M / 256) * (g.N / 256) * 4 >= 3 * (int64_t)cu_count();   // enough 256x256 tiles to fill the chip
+    if (big) return CLS_BIG;
     // a few hundred tokens (any count: rows past M read as zeros through the descriptor and are not stored): the
     // pipelined kernel on 128x256 tiles where their rounds are at least 80 % full (gate|up at 576 tokens: 430 tiles,
     // +10 %; the lm-head's 320 tiles would leave the second round three quarters empty and lose 14 %)
     const int64_t mid_tiles = (int64_t)((g.M + 127) / 128) * (g.N / 256), cus64 = cu_count();
-    const bool mid = !big && whole_n && g.M >= 256 && mid_tiles * 5 >= ((mid_tiles + cus64 - 1) / cus64) * cus64 * 4;
+    const bool mid = whole_n && g.M >= 256 && mid_tiles * 5 >= ((mid_tiles + cus64 - 1) / cus64) * cus64 * 4;
+    return mid ? CLS_MID : CLS_SMALL;
+}
+
+template <int EPI>
+bool dispatch(const GemmArgs& g, hipStream_t st) {
+    const int cls = classify<EPI>(g);
+    if (cls == CLS_STREAM) {
+        run_gemv<EPI>(g, st);
+        return false;
+    }
+    const bool mid = cls == CLS_MID, big = cls == CLS_BIG;
+    const int64_t cus64 = cu_count();
     if (mid) {
         run_gemm<128, 256, 4, 2, EPI, 64, true>(g, 0, g.N / 256, 1, st);
     } else if (big) {
@@ -887,6 +911,16 @@ void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const 
         g.W2 = (const bf16*)wv; g.vc = (bf16*)v_cache; g.N = 3 * d;
         run_gemv<EPI_QKV>(g, st);
         return;
+    }
+    // a few hundred tokens: q | k | v as ONE problem where its 128x256 tiles fill a round (576 tokens: 240 tiles in one
+    // round instead of 320 + 160 on smaller tiles); the same sums, element for element
+    {
+        GemmArgs m3 = g;
+        m3.W2 = (const bf16*)wv; m3.vc = (bf16*)v_cache; m3.N = 3 * d;
+        if (classify<EPI_QKV>(m3) == CLS_MID) {
+            dispatch<EPI_QKV>(m3, st);
+            return;
+        }
     }
     dispatch<EPI_QK>(g, st);
     GemmArgs v{};
