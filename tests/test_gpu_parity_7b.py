@@ -237,3 +237,48 @@ def test_single_token_steps_one_7b_width_layer(B):
                                                      "met" if e_gr.max() <= NORTH_STAR_BF16_TOL else "NOT met"))
         assert max(eq[0], ek[0], ev[0]) <= 2.0 ** -6
         assert rms(e_gr) <= 1.5 * rms(e_ru) and e_gr.max() <= 1.5 * e_ru.max()
+
+
+def test_few_hundred_tokens_run_q_k_v_as_one_launch_with_a_ragged_last_tile():
+    """520 tokens (2 sequences of 260) at the 7B width: the projections of such a launch take q | k | v as one tiled
+    problem (240 tiles of 128 x 256 in one round), whose last row tile holds 8 tokens and whose V third writes the
+    transposed cache from the exchanged-operand layout.  One layer on seeded embeddings of the scale of a hidden
+    state: rotated queries and the appended K and V rows against the oracle's, to the per-layer bar of the test above."""
+    m = dict(WC.model("7b"))
+    nl, nh, dh, d, V = m["n_layers"], m["n_heads"], m["head_dim"], m["d_model"], m["vocab"]
+    B, L, Pn, S = 2, 260, 64, 328
+    w = weights_7b()
+    wd = device_weights(w)
+    m1 = dict(m, n_layers=1)
+    lyr = 17
+    ctx1, cos1, sin1 = make_ctx_from_device(m1, layer_slice(wd, lyr, nl), B, S, L)
+    kv1 = mulo.alloc_kv(ctx1, DEV)
+    d1r = OD.DecoderOracle(m1, layer_slice(w, lyr, nl), cos1, sin1, B, S, round_bf16=True)
+    kb, vb = seeded_cache_rows(m1, Pn, 0)
+    for b in range(B):
+        kv1[0][0, b, :, :Pn] = kb[0].to(DEV)
+        kv1[1][0, b, :, :, :Pn] = vb[0].permute(0, 2, 1).to(DEV)
+        fill_oracle_cache(d1r, b, kb, vb, Pn)
+    x_in = torch.from_numpy(G.normal_logits((B, L, d), 1.0, 0, tag=77)).to(torch.bfloat16)
+    zeros = np.zeros((B, L), np.int32)
+    st = {}
+    d1r.forward(zeros, Pn, embeds=x_in.double().numpy(), stages=st)
+    z_g = torch.empty(B, L, V, device=DEV)
+    mulo.mulo_verify_forward(ctx1, kv1, B, L, Pn, dev(zeros), x_in.to(DEV).contiguous(), z_g)
+    q = torch.empty(B, nh, L, dh, dtype=torch.bfloat16, device=DEV)
+    mulo.mulo_workspace_read(ctx1, mulo.MULO_WS_Q, q)
+    torch.cuda.synchronize()
+    got = dict(q=q.float().cpu().permute(0, 2, 1, 3),                                  # -> [B, L, nh, dh]
+               k=kv1[0][0, :B, :, Pn:Pn + L].float().cpu().permute(0, 2, 1, 3),
+               v=kv1[1][0, :B, :, :, Pn:Pn + L].float().cpu().permute(0, 3, 1, 2))
+    want = dict(q=st["q"][0].reshape(B, L, nh, dh), k=d1r.k[0, :B, Pn:Pn + L], v=d1r.v[0, :B, Pn:Pn + L])
+    for name in ("q", "k", "v"):
+        g_, r_ = got[name].double(), want[name].double()
+        err = (g_ - r_).abs()
+        tol = 2.0 ** -6 * (r_.abs() + 0.1)
+        frac = float((err > tol).double().mean())
+        last = float(err[:, 256:].max())                      # the 4 + 4 tokens of the ragged tile
+        say("  520-token launch, %s: beyond 2^-6 relative %.4f %%, max|err| %.3g (ragged tile %.3g), differ %.3f %%" % (
+            name, 100 * frac, float(err.max()), last, 100 * float((err > 0).double().mean())))
+        assert frac <= 0.005 and float(err.max()) <= 2.0 ** -3 * float(r_.abs().max() + 0.1)
+        assert float((err > 0).double().mean()) < 0.02
