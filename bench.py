@@ -124,7 +124,8 @@ def resample_bench(mulo, ctx, kv, c, B, L, P, V, rate, seed, gen):
     ms_tok = timed(lambda: [mulo.mulo_verify_forward(ctx, kv, B, 1, P + L - 1, tok1, None, z1) for _ in range(20)]) / 20
     print(json.dumps({
         "metric": "re-sampling of one verified block (1 GPU)", "unit": "ms", "higher_is_better": False, "data": "synthetic",
-        "config": {"workload": "%s: last block, B=%d L=%d P=%d, rejection rate %g, radius 1" % (c["name"], B, L, P, rate)},
+        "config": {"workload": "%s: last block, B=%d L=%d P=%d, rejection rate %g, radius 1" % (c["name"], B, L, P, rate),
+                   "stream_copy": int(ctx.cfg.stream_copy)},
         "marked_positions": int(mask.sum()), "islands_per_sequence": cn[:, 0].tolist(), "largest_island": cn[:, 1].tolist(),
         "island_passes": passes, "slots_per_pass": B * cap, "sequential_steps": L - u_start,
         "ms_islands": round(ms_isl, 2), "ms_sequential": round(ms_seq, 2), "ms_single_token_step": round(ms_tok, 3),
@@ -145,7 +146,8 @@ def traffic_from_profile(workload):
         return None
 
 
-def run_workload(mulo, name, wd, rope, steps, warmup, sigma=None, first_block=False, profile="roofline", want_ctx=False):
+def run_workload(mulo, name, wd, rope, steps, warmup, sigma=None, first_block=False, profile="roofline", want_ctx=False,
+                 stream_copy=False):
     """Times `steps` mulo_verify_step calls of workload `name` (inputs resident in HBM) and returns its figures."""
     import torch
 
@@ -161,7 +163,8 @@ def run_workload(mulo, name, wd, rope, steps, warmup, sigma=None, first_block=Fa
     h_blk = L // c["W"] // c["r"]
     n_lo = h_blk * c["w"]
     log("workload %s%s: B=%d L=%d P=%d V=%d" % (c["name"], " (first block)" if first_block else "", B, L, P, V))
-    cfg = mulo.make_cfg(m, B, c["max_seq"], L)
+    # stream_copy: the context keeps the weights once more in the order of the weight-streaming kernels (re-sampling runs)
+    cfg = mulo.make_cfg(m, B, c["max_seq"], L, stream_copy=stream_copy)
     ctx = mulo.mulo_create(cfg, wd, rope[0], rope[1])
     kv = mulo.alloc_kv(ctx, dev, zero=False)
     # cache rows [0, P): seeded N(0, 1) values (a stand-in for the prefilled prefix + committed blocks)
@@ -356,7 +359,8 @@ def main():
     rope = (torch.tensor(cos[:c["max_seq"]], device=dev), torch.tensor(sin[:c["max_seq"]], device=dev))
 
     if a.resample is not None:
-        _, c, ctx, kv, gen = run_workload(mulo, a.workload, wd, rope, 1, 1, a.sigma, profile="none", want_ctx=True)
+        _, c, ctx, kv, gen = run_workload(mulo, a.workload, wd, rope, 1, 1, a.sigma, profile="none", want_ctx=True,
+                                          stream_copy=m["dtype"] == "bf16")
         resample_bench(mulo, ctx, kv, c, c["B"], c["L"], c["max_seq"] - c["L"], m["vocab"], a.resample, c["seed"], gen)
         return
 

@@ -73,11 +73,17 @@ typedef struct {
     int32_t max_batch, max_seq, max_block;
     int32_t dtype;   /* mulo_dtype: type of weights, activations and KV cache */
     float rms_eps;
+    /* MULO_BF16 only, 0 or 1.  1: mulo_create makes a second copy of the projection and lm-head weights inside the
+     * context's workspace, in the order in which the weight-streaming kernels feed them to the matrix instruction
+     * (rows in groups of 16, k in steps of 32, each 1 KB block contiguous), and calls of at most 64 tokens
+     * (single-token steps, island passes) read that copy: whole contiguous KB per load and no lane exchange
+     * (projections of such calls 8-12 % faster).  Costs the size of those weights again (13 GB for a 7B model). */
+    int32_t stream_copy;
 } mulo_model_cfg;
 
 /* Target weights, device pointers in the model dtype, row-major [out, in]
- * (y = x W^T).  The library keeps these pointers (it makes no copy): they must
- * stay valid and unchanged until mulo_destroy.
+ * (y = x W^T).  The library keeps these pointers (and, with stream_copy, a re-ordered copy of its own made at
+ * mulo_create): they must stay valid and unchanged until mulo_destroy.
  *   embed [vocab, d]   attn_norm, ffn_norm [n_layers, d]   final_norm [d]
  *   wq, wk, wv, wo [n_layers, d, d]   w_gate, w_up [n_layers, f, d]
  *   w_down [n_layers, d, f]   lm_head [vocab, d]

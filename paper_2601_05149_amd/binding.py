@@ -29,7 +29,8 @@ class MuloError(RuntimeError):
 
 class ModelCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
-                                         "max_batch", "max_seq", "max_block", "dtype")] + [("rms_eps", C.c_float)]
+                                         "max_batch", "max_seq", "max_block", "dtype")] + [("rms_eps", C.c_float),
+                                                                                             ("stream_copy", C.c_int32)]
 
 
 class Weights(C.Structure):
@@ -111,10 +112,11 @@ def _check(status, where):
         raise MuloError(status, where)
 
 
-def make_cfg(model, max_batch, max_seq, max_block):
+def make_cfg(model, max_batch, max_seq, max_block, stream_copy=False):
+    bf16 = model["dtype"] == "bf16"
     return ModelCfg(model["n_layers"], model["d_model"], model["n_heads"], model["head_dim"], model["d_ffn"],
                     model["vocab"], max_batch, max_seq, max_block,
-                    MULO_BF16 if model["dtype"] == "bf16" else MULO_F32, model.get("rms_eps", 1e-5))
+                    MULO_BF16 if bf16 else MULO_F32, model.get("rms_eps", 1e-5), 1 if (stream_copy and bf16) else 0)
 
 
 MULO_ACCEPT_RATIO, MULO_ACCEPT_TAU = 0, 1

@@ -48,6 +48,7 @@ struct GemmArgs {
     int tile_n0;          // first column tile of the launch (set by the launcher)
     float2* parts;        // LOGITS: softmax statistics per 128-column part of every row [M, n_parts], or nullptr
     int n_parts;
+    bool w_frag;          // weight-streaming launches: W0 .. W2 point at copies in fragment order
     RopeArgs ra;
 };
 
@@ -612,7 +613,7 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 // D[weight row 4 q + i][token l16], q = lane / 16: a lane owns 4 consecutive output columns of one token.  The
 // 8 partial sums are added in a fixed order through LDS and the epilogue runs on pairs of adjacent columns.
 typedef __attribute__((ext_vector_type(4))) float f32x4v;
-template <int EPI, int MT>
+template <int EPI, int MT, bool WFRAG>
 __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     constexpr int NA = EPI == EPI_SWIGLU ? 2 : 1;   // weight matrices (accumulator sets) per column
     // 32-deep k-steps in flight per wavefront: what 16 requests of 16 bytes per lane allow, at least 4 (measured at
@@ -635,9 +636,20 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     const int steps = g.K / 32, per = (steps + 7) / 8;
     const int s0 = wave * per, s1 = s0 + per < steps ? s0 + per : steps;
 
-    // weight row(s) this lane fetches
+    // weight row(s) this lane fetches; with a copy in fragment order (WFRAG) the KB of (16-row block, step) is
+    // contiguous in the MFMA's own lane order: lane l owns its bytes [16 l, 16 l + 16), no exchange afterwards
     const bf16* w[NA];
-    {
+    if constexpr (WFRAG) {
+        int blk = blockIdx.x;   // 16-row block inside its matrix
+        const bf16* base = g.W0;
+        if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
+            const int seg = n_blk / g.d;
+            base = seg == 0 ? g.W0 : seg == 1 ? g.W1 : g.W2;
+            blk -= seg * (g.d / 16);
+        }
+        w[0] = base + (int64_t)blk * steps * 512 + lane * 8;
+        if constexpr (EPI == EPI_SWIGLU) w[1] = g.W1 + (int64_t)blk * steps * 512 + lane * 8;
+    } else {
         int r = n_blk + lrow;
         if constexpr (EPI == EPI_QK || EPI == EPI_QKV) {
             const int seg = n_blk / g.d;                       // a block never straddles q | k | v (d % 16 == 0)
@@ -658,8 +670,10 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     bool has_x[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) has_x[t] = t * 16 + l16 < g.M;
+    if constexpr (!WFRAG) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) w[i] += lchunk * 8;
+        for (int i = 0; i < NA; ++i) w[i] += lchunk * 8;
+    }
     auto to_mfma_order = [&](u32x4 v) {
         u32x4 r;
         r.x = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.x);
@@ -689,7 +703,7 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     auto request = [&](int u, int s) {
         const int sc = s < steps ? s : steps - 1;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * 32);
+        for (int i = 0; i < NA; ++i) wv[i][u] = *reinterpret_cast<const u32x4*>(w[i] + sc * (WFRAG ? 512 : 32));
 #pragma unroll
         for (int t = 0; t < MT; ++t)   // lanes whose token does not exist request nothing (a 4-token launch reads 4 x 64 bytes of the KB)
             if (has_x[t]) xv[t][u] = *reinterpret_cast<const u32x4*>(xg + ((int64_t)t * steps + sc) * 512);
@@ -697,7 +711,7 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
     auto permute = [&](int u, int s, bf16x8 (&wf)[NA], bf16x8 (&xf)[MT]) {
         const bool in_slice = s < s1;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) wf[i] = __builtin_bit_cast(bf16x8, to_mfma_order(wv[i][u]));
+        for (int i = 0; i < NA; ++i) wf[i] = __builtin_bit_cast(bf16x8, WFRAG ? wv[i][u] : to_mfma_order(wv[i][u]));
 #pragma unroll
         for (int t = 0; t < MT; ++t) xf[t] = __builtin_bit_cast(bf16x8, (in_slice && has_x[t]) ? xv[t][u] : zero);
     };
@@ -799,10 +813,34 @@ template <int EPI>
 void run_gemv(const GemmArgs& g, hipStream_t st) {
     const int cols = EPI == EPI_SWIGLU ? g.N / 2 : g.N;
     const dim3 grid((cols + 15) / 16);
-    if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1>), grid, dim3(512), 0, st, g);
-    else if (g.M <= 32) hipLaunchKernelGGL((k_gemv_bf16<EPI, 2>), grid, dim3(512), 0, st, g);
-    else if (g.M <= 48) hipLaunchKernelGGL((k_gemv_bf16<EPI, 3>), grid, dim3(512), 0, st, g);
-    else hipLaunchKernelGGL((k_gemv_bf16<EPI, 4>), grid, dim3(512), 0, st, g);
+    if (g.w_frag) {
+        if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1, true>), grid, dim3(512), 0, st, g);
+        else if (g.M <= 32) hipLaunchKernelGGL((k_gemv_bf16<EPI, 2, true>), grid, dim3(512), 0, st, g);
+        else if (g.M <= 48) hipLaunchKernelGGL((k_gemv_bf16<EPI, 3, true>), grid, dim3(512), 0, st, g);
+        else hipLaunchKernelGGL((k_gemv_bf16<EPI, 4, true>), grid, dim3(512), 0, st, g);
+        return;
+    }
+    if (g.M <= 16) hipLaunchKernelGGL((k_gemv_bf16<EPI, 1, false>), grid, dim3(512), 0, st, g);
+    else if (g.M <= 32) hipLaunchKernelGGL((k_gemv_bf16<EPI, 2, false>), grid, dim3(512), 0, st, g);
+    else if (g.M <= 48) hipLaunchKernelGGL((k_gemv_bf16<EPI, 3, false>), grid, dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((k_gemv_bf16<EPI, 4, false>), grid, dim3(512), 0, st, g);
+}
+
+// one thread per 16-byte piece of the copy: piece p of block (nb, s) is lane p % 64
+__global__ __launch_bounds__(256) void k_pack_weights(const bf16* __restrict__ src, bf16* __restrict__ dst, int layers,
+                                                      int rows, int K) {
+    const int steps = K / 32, nb_per = (rows + 15) / 16;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x, total = (int64_t)layers * nb_per * steps * 64;
+    if (p >= total) return;
+    const int lane = (int)(p & 63);
+    const int64_t blk = p >> 6;
+    const int s = (int)(blk % steps);
+    const int64_t nbl = blk / steps;                     // (layer, 16-row block)
+    const int layer = (int)(nbl / nb_per), nb = (int)(nbl % nb_per);
+    const int row = nb * 16 + (lane & 15), k = s * 32 + (lane >> 4) * 8;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < rows) v = *reinterpret_cast<const u32x4*>(src + ((int64_t)layer * rows + row) * K + k);
+    *reinterpret_cast<u32x4*>(dst + p * 8) = v;
 }
 
 // returns whether the launch ran on the kernels whose wavefront tile is 128 columns wide (whole tiles)
@@ -903,8 +941,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
 }  // namespace
 
 void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
-                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, hipStream_t st) {
+                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, bool w_frag, hipStream_t st) {
     GemmArgs g{};
+    g.w_frag = w_frag && streams_weights(M);
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk;
     g.M = M; g.N = 2 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.d = d; g.ra = ra;
     if (streams_weights(M)) {   // a handful of tokens: q | k | v stream through one launch (xh is in fragment order)
@@ -928,27 +967,36 @@ void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const 
     dispatch<EPI_V>(v, st);
 }
 
-void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, hipStream_t st) {
+void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, bool w_frag, hipStream_t st) {
     GemmArgs g{};
+    g.w_frag = w_frag && streams_weights(M);
     g.A = (const bf16*)a; g.W0 = (const bf16*)w; g.M = M; g.N = N; g.K = K; g.Cf = x;
     dispatch<EPI_RESID>(g, st);
 }
 
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f, int d,
-                             hipStream_t st) {
+                             bool w_frag, hipStream_t st) {
     GemmArgs g{};
+    g.w_frag = w_frag && streams_weights(M);
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wg; g.W1 = (const bf16*)wu; g.M = M; g.N = 2 * f; g.K = d;
     g.Cb = (bf16*)h;
     dispatch<EPI_SWIGLU>(g, st);
 }
 
 bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
-                             hipStream_t st) {
+                             bool w_frag, hipStream_t st) {
     GemmArgs g{};
+    g.w_frag = w_frag && streams_weights(M);
     g.A = (const bf16*)xh; g.W0 = (const bf16*)w; g.M = M; g.N = V; g.K = d; g.Cf = logits;
     g.parts = reinterpret_cast<float2*>(parts);
     g.n_parts = (V + rowparts::PART - 1) / rowparts::PART;
     return dispatch<EPI_LOGITS>(g, st) && parts != nullptr;
+}
+
+void launch_pack_weights(const void* src, void* dst, int layers, int rows, int K, hipStream_t st) {
+    const int64_t pieces = (int64_t)layers * ((rows + 15) / 16) * (K / 32) * 64;
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const bf16*)src, (bf16*)dst,
+                       layers, rows, K);
 }
 
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc, int accumulate,

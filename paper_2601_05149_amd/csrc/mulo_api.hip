@@ -60,6 +60,9 @@ struct mulo_ctx {
     int32_t* isl_pos;    // [maxM] island-parallel re-sampling: cache row of every slot of a pass
     uint8_t* isl_hide;   // [maxM] positions hidden from the queries of a pass
     float* row_parts;    // [maxM, ceil(V / 128)] float pairs: softmax statistics per 128-column part (lm-head epilogue)
+    // cfg.stream_copy: the projection and lm-head weights once more, in the weight-streaming kernels' fragment order
+    // (same layer strides as the caller's, the lm-head padded to whole groups of 16 rows); nullptr without the copy
+    const char *pk_wq, *pk_wk, *pk_wv, *pk_wo, *pk_gate, *pk_up, *pk_down, *pk_lm;
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
@@ -73,11 +76,18 @@ namespace {
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
-constexpr int N_BUF = 17;
+constexpr int N_BUF = 18;
 struct Layout {
     size_t off[N_BUF];
     size_t total;
 };
+
+// elements of the fragment-order copy: wq, wk, wv, wo, w_gate, w_up, w_down of every layer, then the lm-head
+size_t stream_copy_elems(const mulo_model_cfg& c) {
+    const int nl = c.n_layers, d = c.d_model, f = c.d_ffn;
+    return 4 * packed_weight_elems(nl, d, d) + 2 * packed_weight_elems(nl, f, d) + packed_weight_elems(nl, d, f) +
+           packed_weight_elems(1, c.vocab, d);
+}
 
 Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
@@ -87,7 +97,8 @@ Layout plan(const mulo_model_cfg& c) {
     const size_t sizes[N_BUF] = {M * d * 4, M16 * d * e, M * d * e, M16 * d * e, M16 * f * e, M * tmpw * 4,
                               M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
                               c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0,
-                              M * 4, M, c.dtype == MULO_BF16 ? M * ((V + 127) / 128) * 8 : 0};
+                              M * 4, M, c.dtype == MULO_BF16 ? M * ((V + 127) / 128) * 8 : 0,
+                              c.dtype == MULO_BF16 && c.stream_copy ? stream_copy_elems(c) * 2 : 0};
     Layout l{};
     size_t o = 0;
     for (int i = 0; i < N_BUF; ++i) {
@@ -168,31 +179,33 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     hipStream_t st = c->st;
     // a handful of tokens: every bf16 projection streams its weights and takes its token operand in fragment order
     const bool frag = dt == MULO_BF16 && streams_weights(M);
+    const bool wfrag = frag && c->pk_wq != nullptr;
     { PROF(MULO_PROF_NORM_EMBED); launch_embed(c->w.embed, dt, tok, emb, c->x, M, d, V, st); }
     for (int l = 0; l < m.n_layers; ++l) {
         RopeArgs ra{c->w.rope_cos, c->w.rope_sin, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l};
         if (sc) ra.pos_tab = sc->pos_tab;
-        const char* wq = (const char*)c->w.wq + (size_t)l * d * d * e;
-        const char* wk = (const char*)c->w.wk + (size_t)l * d * d * e;
-        const char* wv = (const char*)c->w.wv + (size_t)l * d * d * e;
-        const char* wo = (const char*)c->w.wo + (size_t)l * d * d * e;
-        const char* wg = (const char*)c->w.w_gate + (size_t)l * f * d * e;
-        const char* wu = (const char*)c->w.w_up + (size_t)l * f * d * e;
-        const char* wd = (const char*)c->w.w_down + (size_t)l * d * f * e;
+        // launches that stream the weights read the context's copy in fragment order when it has one (same strides)
+        const char* wq = (wfrag ? c->pk_wq : (const char*)c->w.wq) + (size_t)l * d * d * e;
+        const char* wk = (wfrag ? c->pk_wk : (const char*)c->w.wk) + (size_t)l * d * d * e;
+        const char* wv = (wfrag ? c->pk_wv : (const char*)c->w.wv) + (size_t)l * d * d * e;
+        const char* wo = (wfrag ? c->pk_wo : (const char*)c->w.wo) + (size_t)l * d * d * e;
+        const char* wg = (wfrag ? c->pk_gate : (const char*)c->w.w_gate) + (size_t)l * f * d * e;
+        const char* wu = (wfrag ? c->pk_up : (const char*)c->w.w_up) + (size_t)l * f * d * e;
+        const char* wd = (wfrag ? c->pk_down : (const char*)c->w.w_down) + (size_t)l * d * f * e;
         const char* g_attn = (const char*)c->w.attn_norm + (size_t)l * d * e;
         const char* g_ffn = (const char*)c->w.ffn_norm + (size_t)l * d * e;
         { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_attn, dt, c->xh, M, d, m.rms_eps, frag, st); }
         if (dt == MULO_BF16) {
-            { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, st); }
+            { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, wfrag, st); }
             { PROF(MULO_PROF_ATTENTION);
               if (sc) launch_attention_scattered_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, sc->pos_tab, L, sc->hide,
                                                       sc->P0, sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st);
               else launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim,
                                          m.max_seq, m.max_batch, l, st); }
-            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, st); }
+            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, wfrag, st); }
             { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, frag, st); }
-            { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, st); }
-            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, st); }
+            { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, wfrag, st); }
+            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, wfrag, st); }
         } else {
             const float* xh = (const float*)c->xh;
             { PROF(MULO_PROF_GEMM_QKV);
@@ -215,7 +228,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     }
     { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, frag, st); }
     PROF(MULO_PROF_GEMM_LM_HEAD);
-    if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, st);
+    if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, wfrag ? (const void*)c->pk_lm : c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, wfrag, st);
     launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);
     return false;
 }
@@ -286,6 +299,8 @@ mulo_status mulo_check_model_cfg(const mulo_model_cfg* c) {
     if (c->max_block > c->max_seq) return MULO_ERR_SHAPE;
     if ((c->vocab & 3) || c->vocab > 262144) return MULO_ERR_UNSUPPORTED;
     if ((int64_t)c->max_batch * c->max_block > (1 << 22)) return MULO_ERR_UNSUPPORTED;
+    if (c->stream_copy != 0 && c->stream_copy != 1) return MULO_ERR_RANGE;
+    if (c->stream_copy && c->dtype != MULO_BF16) return MULO_ERR_UNSUPPORTED;
     if (c->dtype == MULO_BF16) {
         if (c->head_dim != 64 && c->head_dim != 128) return MULO_ERR_UNSUPPORTED;
         if ((c->d_model % 128) || (c->d_ffn % 64) || c->d_ffn < 128 || (c->max_seq % 8) || (c->max_block % 4))
@@ -368,6 +383,30 @@ mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* 
     c->isl_pos = (int32_t*)(b + l.off[14]);
     c->isl_hide = (uint8_t*)(b + l.off[15]);
     c->row_parts = c->esz == 2 ? (float*)(b + l.off[16]) : nullptr;
+    c->pk_wq = c->pk_wk = c->pk_wv = c->pk_wo = c->pk_gate = c->pk_up = c->pk_down = c->pk_lm = nullptr;
+    if (cfg->stream_copy) {   // bf16 (checked): the second copy of the weights, made once on the context's stream
+        const int nl = cfg->n_layers, d = cfg->d_model, f = cfg->d_ffn;
+        char* p = b + l.off[17];
+        auto take = [&](const void* src, int layers, int rows, int K) {
+            const char* at = p;
+            launch_pack_weights(src, p, layers, rows, K, c->st);
+            p += packed_weight_elems(layers, rows, K) * 2;
+            return at;
+        };
+        c->pk_wq = take(w->wq, nl, d, d);
+        c->pk_wk = take(w->wk, nl, d, d);
+        c->pk_wv = take(w->wv, nl, d, d);
+        c->pk_wo = take(w->wo, nl, d, d);
+        c->pk_gate = take(w->w_gate, nl, f, d);
+        c->pk_up = take(w->w_up, nl, f, d);
+        c->pk_down = take(w->w_down, nl, d, f);
+        c->pk_lm = take(w->lm_head, 1, cfg->vocab, d);
+        if (check_launch() != MULO_OK) {
+            (void)hipFree(c->base);
+            delete c;
+            return MULO_ERR_HIP;
+        }
+    }
     *out = c;
     return MULO_OK;
 }

@@ -105,18 +105,24 @@ void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int 
                     hipStream_t st);
 
 // bf16 MFMA GEMMs, C = A[M,K] * W[N,K]^T with fused epilogues
+// w_frag: the weight pointers are the context's copies in fragment order (stream_copy; only launches that stream)
 void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
-                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra,
+                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, bool w_frag,
                           hipStream_t st);
-void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K,
+void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, bool w_frag,
                             hipStream_t st);
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f,
-                             int d, hipStream_t st);
+                             int d, bool w_frag, hipStream_t st);
+// Copies `layers` bf16 matrices [rows, K] (contiguous, rows % 16 == 0 or layers == 1) into fragment order: rows in
+// groups of 16, k in steps of 32, the KB of (group, step) contiguous with lane 16 c + r holding k 8 c .. 8 c + 7 of
+// row r; rows past the last are zeros.  dst holds layers * ceil16(rows) * K elements.
+void launch_pack_weights(const void* src, void* dst, int layers, int rows, int K, hipStream_t st);
+inline size_t packed_weight_elems(int layers, int rows, int K) { return (size_t)layers * ((rows + 15) / 16 * 16) * K; }
 // parts: nullptr, or float pairs [M, ceil(V / 128)] that receive the softmax statistics of every 128-column part of
 // every row (row_parts.h); returns whether they were written (only the kernels whose wavefront tile is 128 columns
 // wide produce them)
 bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
-                             hipStream_t st);
+                             bool w_frag, hipStream_t st);
 size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim);   // partial results of the key split
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
                            int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,

@@ -15,10 +15,10 @@ def say(msg):
     print(msg, flush=True)
 
 
-def make_ctx(model, weights, max_batch, max_seq, max_block):
+def make_ctx(model, weights, max_batch, max_seq, max_block, stream_copy=False):
     from workloads import generators as G
     cos, sin = G.rope_table(max_seq, model["head_dim"])
-    cfg = mulo.make_cfg(model, max_batch, max_seq, max_block)
+    cfg = mulo.make_cfg(model, max_batch, max_seq, max_block, stream_copy)
     key = id(weights)
     if key not in _DEVW:                       # one upload per weight set (13 GB for the 7B-class model)
         _DEVW[key] = (weights, {k: v.to(DEV) for k, v in weights.items()})
@@ -27,12 +27,12 @@ def make_ctx(model, weights, max_batch, max_seq, max_block):
     return ctx, cos, sin
 
 
-def make_ctx_from_device(model, wd, max_batch, max_seq, max_block):
+def make_ctx_from_device(model, wd, max_batch, max_seq, max_block, stream_copy=False):
     """Context over weight tensors that already live on the device (e.g. one-layer
     slices of a larger model)."""
     from workloads import generators as G
     cos, sin = G.rope_table(max_seq, model["head_dim"])
-    cfg = mulo.make_cfg(model, max_batch, max_seq, max_block)
+    cfg = mulo.make_cfg(model, max_batch, max_seq, max_block, stream_copy)
     ctx = mulo.mulo_create(cfg, wd, torch.tensor(cos, device=DEV), torch.tensor(sin, device=DEV))
     return ctx, cos, sin
 

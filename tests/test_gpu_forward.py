@@ -237,15 +237,15 @@ def test_forward_7b_hires_full_launch_sampled_sequence():
     del ctx, ctx1
 
 
-@pytest.mark.parametrize("dh,nh", [(64, 4), (128, 2)])
-def test_forward_single_token_steps_with_split_keys(dh, nh):
+@pytest.mark.parametrize("dh,nh,copy", [(64, 4, False), (128, 2, False), (128, 2, True)])
+def test_forward_single_token_steps_with_split_keys(dh, nh, copy):
     """Decode shape: one token per sequence against a cache of several key tiles, so that the keys are dealt
     to several workgroups per head and combined (and the projections run in the weight-streaming kernel).
     Cache lengths 199 .. 202 straddle a tile boundary (64-key tiles, the last one partly filled)."""
     m = dict(n_layers=2, d_model=dh * nh, n_heads=nh, head_dim=dh, d_ffn=512, vocab=1024, dtype="bf16", rms_eps=1e-5)
     B, Pn = 3, 199
     w = G.make_weights(m, seed=5)
-    ctx, cos, sin = make_ctx(m, w, B, 208, 200)
+    ctx, cos, sin = make_ctx(m, w, B, 208, 200, stream_copy=copy)   # copy: the weights once more in fragment order
     kv = mulo.alloc_kv(ctx, DEV)
     dr, du = pair(m, w, cos, sin, B, 208)
     pre = G.uniform_tokens((B, Pn), m["vocab"], 5, tag=0)
@@ -267,8 +267,8 @@ def frag_to_rows(buf, M, K):
     return buf.reshape(-1)[idx]
 
 
-@pytest.mark.parametrize("B,L", [(3, 1), (4, 13), (2, 32)])
-def test_forward_few_tokens_keeps_its_operands_in_fragment_order(B, L):
+@pytest.mark.parametrize("B,L,copy", [(3, 1, False), (4, 13, False), (2, 32, False), (3, 1, True), (4, 13, True)])
+def test_forward_few_tokens_keeps_its_operands_in_fragment_order(B, L, copy):
     """Launches of at most 64 tokens (one, four and four token groups of 16; 3, 52 and 64 tokens) run every projection
     in the weight-streaming kernel, whose token operand the producing kernels leave in the matrix instruction's own
     order.  One layer: the attention output and silu(gate) * up read back through mulo_workspace_read, put back in
@@ -276,7 +276,7 @@ def test_forward_few_tokens_keeps_its_operands_in_fragment_order(B, L):
     m = dict(n_layers=1, d_model=256, n_heads=2, head_dim=128, d_ffn=512, vocab=1024, dtype="bf16", rms_eps=1e-5)
     Pn, S, M = 70, 112, B * L
     w = G.make_weights(m, seed=11)
-    ctx, cos, sin = make_ctx(m, w, B, S, 72)
+    ctx, cos, sin = make_ctx(m, w, B, S, 72, stream_copy=copy)
     kv = mulo.alloc_kv(ctx, DEV)
     dr, du = pair(m, w, cos, sin, B, S)
     pre = G.uniform_tokens((B, Pn), m["vocab"], 11, tag=0)

@@ -25,7 +25,7 @@ pytestmark = pytest.mark.gpu
 def _device_run(m, w, B, Pn, H, W, mask, seed, ctr, cap_extra=0, n_passes=None):
     V, L = m["vocab"], H * W
     max_seq = (Pn + L + 15) // 8 * 8
-    ctx, cos, sin = make_ctx(m, w, B, max_seq, max(Pn, L))
+    ctx, cos, sin = make_ctx(m, w, B, max_seq, max(Pn, L), stream_copy=m["dtype"] == "bf16")
     kv = mulo.alloc_kv(ctx, DEV)
     prefix = G.uniform_tokens((B, Pn), V, 0, tag=0)
     draft = G.uniform_tokens((B, L), V, 1, tag=0)

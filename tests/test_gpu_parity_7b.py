@@ -197,8 +197,8 @@ def test_step_at_the_timed_7b_blocks_vs_oracle(name):
     del ctx
 
 
-@pytest.mark.parametrize("B", [4, 52])
-def test_single_token_steps_one_7b_width_layer(B):
+@pytest.mark.parametrize("B,copy", [(4, False), (52, False), (4, True), (52, True)])
+def test_single_token_steps_one_7b_width_layer(B, copy):
     """Decode shape at the 7B width: B single-token queries (M = 4: one token group; M = 52: four groups, the
     island-pass size) through the weight-streaming kernel with K = 4096 (q | k | v, out) and K = 11008 (down), one
     layer.  The kernel's direct outputs (rotated query, appended K and V rows) within 2^-6 relative of the
@@ -208,7 +208,7 @@ def test_single_token_steps_one_7b_width_layer(B):
     nh, dh, V = m["n_heads"], m["head_dim"], m["vocab"]
     w = G.make_weights(m, seed=11)
     Pn, S = 68, 72
-    ctx, cos, sin = make_ctx(m, w, B, S, Pn)
+    ctx, cos, sin = make_ctx(m, w, B, S, Pn, stream_copy=copy)
     kv = mulo.alloc_kv(ctx, DEV)
     dr = OD.DecoderOracle(m, w, cos, sin, B, S, round_bf16=True)
     du = OD.DecoderOracle(m, w, cos, sin, B, S, round_bf16=False)

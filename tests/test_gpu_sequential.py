@@ -25,7 +25,7 @@ def _run(m, B, Pn, L, mask, t0, seed, ctr, round_bf16, logit_tol):
     V = m["vocab"]
     w = G.make_weights(m, seed=0, threads=4)
     max_seq = (Pn + L + 15) // 8 * 8
-    ctx, cos, sin = make_ctx(m, w, B, max_seq, (max(Pn, L) + 3) // 4 * 4)
+    ctx, cos, sin = make_ctx(m, w, B, max_seq, (max(Pn, L) + 3) // 4 * 4, stream_copy=m["dtype"] == "bf16")
     kv = mulo.alloc_kv(ctx, DEV)
     prefix = G.uniform_tokens((B, Pn), V, 0, tag=0)
     draft = G.uniform_tokens((B, L), V, 1, tag=0)

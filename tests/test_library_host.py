@@ -54,6 +54,18 @@ def test_model_cfg_checks(lib):
     assert lib.mulo_check_model_cfg(C.byref(bad)) == 2          # block longer than the cache
     assert lib.mulo_check_model_cfg(None) == 1
     assert lib.mulo_workspace_bytes(C.byref(bad)) == 0
+    # the second copy of the weights for the weight-streaming kernels: bf16 only, 0 or 1, and it is part of the workspace
+    plain = mulo.make_cfg(c["model"], 4, c["max_seq"], 256)
+    copy = mulo.make_cfg(c["model"], 4, c["max_seq"], 256, stream_copy=True)
+    assert lib.mulo_check_model_cfg(C.byref(copy)) == 0
+    m = c["model"]
+    w_bytes = 2 * (m["n_layers"] * (4 * m["d_model"] ** 2 + 3 * m["d_ffn"] * m["d_model"]) + m["vocab"] * m["d_model"])
+    assert lib.mulo_workspace_bytes(C.byref(copy)) - lib.mulo_workspace_bytes(C.byref(plain)) == w_bytes
+    copy.stream_copy = 2
+    assert lib.mulo_check_model_cfg(C.byref(copy)) == 3
+    f32 = mulo.make_cfg(WC.get("cfg1")["model"], 1, 296, 256)
+    f32.stream_copy = 1
+    assert lib.mulo_check_model_cfg(C.byref(f32)) == 6
 
 
 def test_step_param_checks(lib):
