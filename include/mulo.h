@@ -77,7 +77,9 @@ typedef struct {
      * context's workspace, in the order in which the weight-streaming kernels feed them to the matrix instruction
      * (rows in groups of 16, k in steps of 32, each 1 KB block contiguous), and calls of at most 64 tokens
      * (single-token steps, island passes) read that copy: whole contiguous KB per load and no lane exchange
-     * (projections of such calls 8-12 % faster).  Costs the size of those weights again (13 GB for a 7B model). */
+     * (projections of such calls 8-12 % faster); calls of 65 to 256 tokens (island passes of larger batches) then stream
+     * the weights as well instead of running on the tiled kernels.  Costs the size of those weights again (13 GB for a
+     * 7B model) plus the partial sums of a 256-token call. */
     int32_t stream_copy;
 } mulo_model_cfg;
 
@@ -322,8 +324,8 @@ MULO_API mulo_status mulo_resample_islands(mulo_ctx *ctx, mulo_kv *kv, int32_t B
  *   MULO_WS_Q         T [B, n_heads, L, head_dim]  rotated queries of the last layer
  *   MULO_WS_ATTN      T [M, d]             attention output of the last layer (input of the out projection)
  *   MULO_WS_FFN       T [M, d_ffn]         silu(gate) * up of the last layer (input of the down projection)
- * After a bf16 call of at most 64 tokens (M <= 64: single-token steps, island passes) NORMED, ATTN and FFN are not
- * row-major: such calls keep the token operand of every projection in the order the matrix instruction reads it
+ * After a bf16 call of at most 64 tokens (256 with stream_copy: single-token steps, island passes) NORMED, ATTN and
+ * FFN are not row-major: such calls keep the token operand of every projection in the order the matrix instruction reads it
  * (tokens in groups of 16, columns in steps of 32; element (m, k) of a [M, K] operand sits at
  * ((m / 16) * (K / 32) + k / 32) * 512 + ((k % 32) / 8 * 16 + m % 16) * 8 + k % 8).
  *   dst  device pointer, at least `bytes` bytes

@@ -422,11 +422,11 @@ size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim) {
 
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
                            int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch, int layer,
-                           hipStream_t st) {
+                           bool frag_out, hipStream_t st) {
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = L; a.P = P; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
-    a.frag = streams_weights(B * L) ? 1 : 0;   // the out projection of such a launch streams its weights
+    a.frag = frag_out ? 1 : 0;   // the out projection of such a launch streams its weights
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
     // one query per sequence: too few (sequence, head) pairs to fill the chip, so the keys are split as well
     a.nsplit = 1;
@@ -445,11 +445,11 @@ void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cac
 void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out,
                                      float* scratch, int B, const int32_t* pos_tab, int cap, const uint8_t* hide,
                                      int P0, int Lblk, int n_heads, int head_dim, int max_seq, int max_batch,
-                                     int layer, hipStream_t st) {
+                                     int layer, bool frag_out, hipStream_t st) {
     AttnArgs a{};
     a.q = (const bf16*)q; a.kc = (const bf16*)k_cache; a.vc = (const bf16*)v_cache; a.out = (bf16*)out;
     a.B = B; a.L = cap; a.P = P0; a.nh = n_heads; a.max_seq = max_seq; a.max_batch = max_batch; a.layer = layer;
-    a.frag = streams_weights(B * cap) ? 1 : 0;
+    a.frag = frag_out ? 1 : 0;
     a.scale_log2 = LOG2E / sqrtf((float)head_dim);
     a.pos_tab = pos_tab; a.hide = hide; a.P0 = P0; a.Lblk = Lblk;
     // the slots of a sequence are the queries of one workgroup (128 per tile), which streams the sequence's rows

@@ -48,7 +48,10 @@ struct GemmArgs {
     int tile_n0;          // first column tile of the launch (set by the launcher)
     float2* parts;        // LOGITS: softmax statistics per 128-column part of every row [M, n_parts], or nullptr
     int n_parts;
+    bool stream;          // A is in fragment order: the launch runs in the weight-streaming kernels
     bool w_frag;          // weight-streaming launches: W0 .. W2 point at copies in fragment order
+    float* ksums;         // more than STREAM_SHARED_MIN_TOKENS tokens: sums of the K slices [ksplit, M, columns]
+    int ksplit;           // set by the launcher
     RopeArgs ra;
 };
 
@@ -600,6 +603,51 @@ void run_gemm(GemmArgs g, int tile_n0, int tiles_n, int blocks_per_cu, hipStream
 }
 
 
+// Epilogue of the weight-streaming kernels on two adjacent output columns n, n + 1 of token m (v1: the up sums of
+// gate|up).  The same five fused epilogues as the tiled kernels; a bf16 operand of a following projection is written
+// in fragment order.
+template <int EPI>
+__device__ __forceinline__ void stream_epilogue(const GemmArgs& g, int m, int n, const float (&v0)[2], const float (&v1)[2]) {
+    if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
+        float* dst = g.Cf + (int64_t)m * g.N + n;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v0[e] : v0[e];
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        const int f = g.N / 2;
+        bf16* dst = g.Cb + frag_index(m, n, f);   // the down projection streams too: its token operand, fragment order
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
+    } else {
+        const TokPlace pl = place(g.ra, m);
+        if (pl.pos < 0) return;   // an unused slot of a scattered launch
+        const int dh = g.ra.head_dim, pos = pl.pos;
+        if (EPI == EPI_QK || (EPI == EPI_QKV && n < 2 * g.d)) {
+            const int seg = n / g.d, c = n - seg * g.d;
+            const int hd = c / dh, cc = c % dh;
+            const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
+            bf16* dst;
+            if (seg == 0) {
+                dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
+            } else {
+                const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
+            }
+            dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
+            dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
+        } else {   // V: transposed cache
+            const int nv = EPI == EPI_QKV ? n - 2 * g.d : n, nlim = EPI == EPI_QKV ? g.d : g.N;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int hd = (nv + e) / dh, cc = (nv + e) % dh;
+                const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
+                if (nv + e < nlim) g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = __float2bfloat16(v0[e]);
+            }
+        }
+    }
+}
+
 // ---- up to 64 tokens (single-token decoding of a few sequences, island passes): weight-streaming kernel ----
 // The work is reading every weight once, so nothing is staged: a workgroup owns 16 output columns (for
 // gate|up: 16 feed-forward columns = 16 gate rows + 16 up rows), its 8 wavefronts split K, and every lane
@@ -767,50 +815,174 @@ __global__ __launch_bounds__(512) void k_gemv_bf16(const GemmArgs g) {
             v0[e] = sum0;
             v1[e] = sum1;
         }
-        const int n = n_blk + 4 * q + 2 * pr;
-        if constexpr (EPI == EPI_RESID || EPI == EPI_LOGITS) {
-            float* dst = g.Cf + (int64_t)m * g.N + n;
+        stream_epilogue<EPI>(g, m, n_blk + 4 * q + 2 * pr, v0, v1);
+    }
+}
+
+// ---- 65 to 256 tokens with the weight copy in fragment order: the token operand goes through LDS ----
+// With several token groups the kernel above spends its time on the token operand: every workgroup (16 columns) reads
+// all of it through its vector L1, a KB per token group and KB of weights.  Here a workgroup owns 128 columns (a
+// wavefront 16 of them) and a slice of K: the slice's token operand, which arrives in fragment order, is copied to LDS
+// once per workgroup, 8 k-steps at a time, and every wavefront feeds its MFMAs from there (one 16-byte LDS read per
+// lane and token group); only the weights, contiguous KB blocks of the fragment-order copy, come through the memory
+// pipeline, 8 steps in flight per wavefront.  K is dealt to `ksplit` workgroups per column group; each leaves its sums
+// [M, 128] in `ksums`, and k_stream_finish adds the slices in index order and runs the epilogue (no float atomics:
+// the result does not depend on which workgroup finishes first).  Gate|up and q|k|v are concatenations of their weight
+// matrices (`seg_rows` rows each) along the column axis.
+template <int MTB>
+__global__ __launch_bounds__(512) void k_gemv_shared(const GemmArgs g, int ncols, int seg_rows, int ncg) {
+    constexpr int CH = 8;                         // k-steps per LDS chunk = weight steps in flight per wavefront
+    constexpr int PIECES = CH * MTB * 64 / 512;   // 16-byte pieces of a chunk per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // fragment (group t, step j) at (t CH + j) KB
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, q = lane >> 4;
+    const int cg = blockIdx.x % ncg, kw = blockIdx.x / ncg;   // neighbouring workgroups share a K slice of the token operand
+    const int n_w = cg * 128 + wave * 16;                     // this wavefront's first column
+    const int steps = g.K / 32, per = (steps + g.ksplit - 1) / g.ksplit;
+    const int s0 = kw * per, s1 = s0 + per < steps ? s0 + per : steps;
+    const int n_groups = (g.M + 15) >> 4;
+
+    const bf16* w;
+    {
+        const int last = (ncols - 1) / 16 * 16;               // a wavefront past the last column re-reads the last block
+        const int n_c = n_w < last ? n_w : last;
+        const int seg = n_c / seg_rows;                        // 16 columns never straddle two matrices (seg_rows % 16 == 0)
+        w = (seg == 0 ? g.W0 : seg == 1 ? g.W1 : g.W2) + (int64_t)((n_c - seg * seg_rows) / 16) * steps * 512 + lane * 8;
+    }
+    f32x4v acc[MTB];
 #pragma unroll
-            for (int e = 0; e < 2; ++e)
-                if (n + e < g.N) dst[e] = EPI == EPI_RESID ? dst[e] + v0[e] : v0[e];
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            const int f = g.N / 2;
-            bf16* dst = g.Cb + frag_index(m, n, f);   // the down projection streams too: its token operand, fragment order
+    for (int t = 0; t < MTB; ++t) acc[t] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    u32x4 wv[CH], xr[PIECES];
+    auto request = [&](int u, int s) {
+        const int sc = s < steps ? s : steps - 1;
+        wv[u] = *reinterpret_cast<const u32x4*>(w + (int64_t)sc * 512);
+    };
+    // chunk of steps [sc0, sc0 + CH): piece p = ((t CH + j) 64 + lane position); steps past the slice and token groups
+    // that do not exist are zeros (tokens past M inside the last group are whatever the buffer holds: they only reach
+    // accumulator columns that are never stored)
+    auto xload = [&](int sc0) {
 #pragma unroll
-            for (int e = 0; e < 2; ++e)
-                if (n + e < f) dst[e] = __float2bfloat16(silu(v0[e]) * v1[e]);
-        } else {
-            const TokPlace pl = place(g.ra, m);
-            if (pl.pos < 0) return;   // an unused slot of a scattered launch
-            const int dh = g.ra.head_dim, pos = pl.pos;
-            if (EPI == EPI_QK || (EPI == EPI_QKV && n < 2 * g.d)) {
-                const int seg = n / g.d, c = n - seg * g.d;
-                const int hd = c / dh, cc = c % dh;
-                const float cs = g.ra.cos[(int64_t)pos * (dh / 2) + (cc >> 1)], sn = g.ra.sin[(int64_t)pos * (dh / 2) + (cc >> 1)];
-                bf16* dst;
-                if (seg == 0) {
-                    dst = g.Cb + (((int64_t)pl.b * g.ra.n_heads + hd) * g.ra.L + pl.jj) * dh + cc;
-                } else {
-                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
-                    dst = g.kc + (hb * g.ra.max_seq + pos) * dh + cc;
-                }
-                dst[0] = __float2bfloat16(v0[0] * cs - v0[1] * sn);
-                dst[1] = __float2bfloat16(v0[0] * sn + v0[1] * cs);
-            } else {   // V: transposed cache
-                const int nv = EPI == EPI_QKV ? n - 2 * g.d : n, nlim = EPI == EPI_QKV ? g.d : g.N;
+        for (int i = 0; i < PIECES; ++i) {
+            const int p = tid + i * 512, t = p / (CH * 64), j = (p / 64) % CH;
+            xr[i] = zero;
+            if (t < n_groups && sc0 + j < s1)
+                xr[i] = *reinterpret_cast<const u32x4*>(g.A + ((int64_t)t * steps + sc0 + j) * 512 + (p & 63) * 8);
+        }
+    };
+    auto xstore = [&]() {
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int hd = (nv + e) / dh, cc = (nv + e) % dh;
-                    const int64_t hb = ((int64_t)g.ra.layer * g.ra.max_batch + pl.bc) * g.ra.n_heads + hd;
-                    if (nv + e < nlim) g.vc[(hb * dh + cc) * g.ra.max_seq + pos] = __float2bfloat16(v0[e]);
-                }
+        for (int i = 0; i < PIECES; ++i) *reinterpret_cast<u32x4*>(smem + (size_t)(tid + i * 512) * 16) = xr[i];
+    };
+    auto chunk = [&](int sc0, auto req) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[u]);
+            if constexpr (decltype(req)::value) request(u, sc0 + CH + u);
+#pragma unroll
+            for (int t = 0; t < MTB; ++t) {
+                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(smem + (size_t)((t * CH + u) * 64 + lane) * 16);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[t], 0, 0, 0);
+            }
+        }
+    };
+    if (s0 < s1) {   // uniform over the workgroup
+#pragma unroll
+        for (int u = 0; u < CH; ++u) request(u, s0 + u);
+        xload(s0);
+        xstore();
+        __syncthreads();
+        int sc0 = s0;
+        for (; sc0 + CH < s1; sc0 += CH) {
+            xload(sc0 + CH);
+            chunk(sc0, std::true_type{});
+            __syncthreads();   // every wavefront has read the chunk
+            xstore();
+            __syncthreads();
+        }
+        chunk(sc0, std::false_type{});   // the last chunk requests nothing
+    }
+    // this slice's sums: D[weight row 4 q + i][token l16] -> ksums[kw][m][n_w + 4 q + i]
+#pragma unroll
+    for (int t = 0; t < MTB; ++t) {
+        const int m = t * 16 + l16, n = n_w + 4 * q;
+        if (m < g.M && n < ncols) {
+            float* dst = g.ksums + ((int64_t)kw * g.M + m) * ncols + n;
+            if (n + 4 <= ncols) {
+                *reinterpret_cast<f32x4v*>(dst) = acc[t];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < ncols) dst[i] = acc[t][i];
             }
         }
     }
 }
 
+// adds the K slices of two adjacent columns of a token in index order and runs the projection's epilogue
+template <int EPI>
+__global__ __launch_bounds__(256) void k_stream_finish(const GemmArgs g, int ncols) {
+    const int cols = EPI == EPI_SWIGLU ? ncols / 2 : ncols;   // gate|up: the up sums of column n sit at column f + n
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int pairs = cols / 2;
+    const int m = (int)(idx / pairs), n = 2 * (int)(idx % pairs);
+    if (m >= g.M) return;
+    float v0[2] = {0.f, 0.f}, v1[2] = {0.f, 0.f};
+    for (int kw = 0; kw < g.ksplit; ++kw) {
+        const float* src = g.ksums + ((int64_t)kw * g.M + m) * ncols + n;
+        const float2 a = *reinterpret_cast<const float2*>(src);
+        v0[0] += a.x;
+        v0[1] += a.y;
+        if constexpr (EPI == EPI_SWIGLU) {
+            const float2 b = *reinterpret_cast<const float2*>(src + cols);
+            v1[0] += b.x;
+            v1[1] += b.y;
+        }
+    }
+    stream_epilogue<EPI>(g, m, n, v0, v1);
+}
+
+template <int EPI>
+void run_gemv_shared(GemmArgs g, hipStream_t st) {
+    const int ncols = g.N, seg_rows = (EPI == EPI_QKV || EPI == EPI_QK) ? g.d : EPI == EPI_SWIGLU ? g.N / 2 : g.N;
+    const int ncg = (ncols + 127) / 128;
+    g.ksplit = stream_ksplit(ncols, g.K);
+    const dim3 grid(ncg * g.ksplit);
+    auto launch = [&](auto kern, int mtb) {
+        static int attr_state = 0;   // one per kernel instantiation (the lambda's call operator is a template)
+        if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), mtb * 8 * 1024, &attr_state)) return;
+        hipLaunchKernelGGL(kern, grid, dim3(512), (size_t)mtb * 8 * 1024, st, g, ncols, seg_rows, ncg);
+    };
+    switch ((g.M + 15) / 16) {   // one instantiation per number of token groups: LDS reads and MFMAs follow it
+        case 1: case 2: case 3: case 4: launch(k_gemv_shared<4>, 4); break;
+        case 5: launch(k_gemv_shared<5>, 5); break;
+        case 6: launch(k_gemv_shared<6>, 6); break;
+        case 7: launch(k_gemv_shared<7>, 7); break;
+        case 8: launch(k_gemv_shared<8>, 8); break;
+        case 9: launch(k_gemv_shared<9>, 9); break;
+        case 10: launch(k_gemv_shared<10>, 10); break;
+        case 11: launch(k_gemv_shared<11>, 11); break;
+        case 12: launch(k_gemv_shared<12>, 12); break;
+        case 13: launch(k_gemv_shared<13>, 13); break;
+        case 14: launch(k_gemv_shared<14>, 14); break;
+        case 15: launch(k_gemv_shared<15>, 15); break;
+        default: launch(k_gemv_shared<16>, 16); break;
+    }
+    const int cols = EPI == EPI_SWIGLU ? ncols / 2 : ncols;
+    const int64_t threads = (int64_t)g.M * (cols / 2);
+    hipLaunchKernelGGL((k_stream_finish<EPI>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, g, ncols);
+}
+
 template <int EPI>
 void run_gemv(const GemmArgs& g, hipStream_t st) {
+    if (g.M > STREAM_SHARED_MIN_TOKENS && g.w_frag && g.ksums) {   // several token groups: the token operand goes through LDS
+        run_gemv_shared<EPI>(g, st);
+        return;
+    }
+    if (g.M > STREAM_MAX_TOKENS) {   // the kernel below holds four token groups
+        note_hip_error(hipErrorInvalidValue);
+        return;
+    }
     const int cols = EPI == EPI_SWIGLU ? g.N / 2 : g.N;
     const dim3 grid((cols + 15) / 16);
     if (g.w_frag) {
@@ -847,7 +1019,7 @@ __global__ __launch_bounds__(256) void k_pack_weights(const bf16* __restrict__ s
 enum { CLS_STREAM, CLS_BIG, CLS_MID, CLS_SMALL };
 template <int EPI>
 int classify(const GemmArgs& g) {
-    if (streams_weights(g.M)) return CLS_STREAM;   // a handful of tokens: stream the weights (A is in fragment order)
+    if (g.stream) return CLS_STREAM;   // a handful of tokens: stream the weights (A is in fragment order)
     // large problems: 256x256 tiles, 8 wavefronts (4x2, 64x128 each, two per SIMD); small: 128x128, 4 wavefronts
     // (whole tiles only: their operand rows are addressed from scalar bases; a q|k|v tile must not straddle two weights)
     const bool whole_n = g.N % 256 == 0 && ((EPI == EPI_QK || EPI == EPI_QKV) ? g.d % 256 == 0 : true) &&
@@ -941,12 +1113,12 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
 }  // namespace
 
 void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
-                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, bool w_frag, hipStream_t st) {
+                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, const StreamMode& sm, hipStream_t st) {
     GemmArgs g{};
-    g.w_frag = w_frag && streams_weights(M);
+    g.stream = sm.stream; g.w_frag = sm.w_frag; g.ksums = sm.ksums;
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wq; g.W1 = (const bf16*)wk;
     g.M = M; g.N = 2 * d; g.K = d; g.Cb = (bf16*)q_out; g.kc = (bf16*)k_cache; g.d = d; g.ra = ra;
-    if (streams_weights(M)) {   // a handful of tokens: q | k | v stream through one launch (xh is in fragment order)
+    if (g.stream) {   // a handful of tokens: q | k | v stream through one launch (xh is in fragment order)
         g.W2 = (const bf16*)wv; g.vc = (bf16*)v_cache; g.N = 3 * d;
         run_gemv<EPI_QKV>(g, st);
         return;
@@ -967,26 +1139,26 @@ void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const 
     dispatch<EPI_V>(v, st);
 }
 
-void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, bool w_frag, hipStream_t st) {
+void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, const StreamMode& sm, hipStream_t st) {
     GemmArgs g{};
-    g.w_frag = w_frag && streams_weights(M);
+    g.stream = sm.stream; g.w_frag = sm.w_frag; g.ksums = sm.ksums;
     g.A = (const bf16*)a; g.W0 = (const bf16*)w; g.M = M; g.N = N; g.K = K; g.Cf = x;
     dispatch<EPI_RESID>(g, st);
 }
 
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f, int d,
-                             bool w_frag, hipStream_t st) {
+                             const StreamMode& sm, hipStream_t st) {
     GemmArgs g{};
-    g.w_frag = w_frag && streams_weights(M);
+    g.stream = sm.stream; g.w_frag = sm.w_frag; g.ksums = sm.ksums;
     g.A = (const bf16*)xh; g.W0 = (const bf16*)wg; g.W1 = (const bf16*)wu; g.M = M; g.N = 2 * f; g.K = d;
     g.Cb = (bf16*)h;
     dispatch<EPI_SWIGLU>(g, st);
 }
 
 bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
-                             bool w_frag, hipStream_t st) {
+                             const StreamMode& sm, hipStream_t st) {
     GemmArgs g{};
-    g.w_frag = w_frag && streams_weights(M);
+    g.stream = sm.stream; g.w_frag = sm.w_frag; g.ksums = sm.ksums;
     g.A = (const bf16*)xh; g.W0 = (const bf16*)w; g.M = M; g.N = V; g.K = d; g.Cf = logits;
     g.parts = reinterpret_cast<float2*>(parts);
     g.n_parts = (V + rowparts::PART - 1) / rowparts::PART;

@@ -63,6 +63,7 @@ struct mulo_ctx {
     // cfg.stream_copy: the projection and lm-head weights once more, in the weight-streaming kernels' fragment order
     // (same layer strides as the caller's, the lm-head padded to whole groups of 16 rows); nullptr without the copy
     const char *pk_wq, *pk_wk, *pk_wv, *pk_wo, *pk_gate, *pk_up, *pk_down, *pk_lm;
+    float* ksums;        // with the copy: sums of the K slices of a 65..256-token launch's projections
     void* base;      // single allocation
     // optional per-launch timing (mulo_profile)
     bool prof_on = false;
@@ -76,7 +77,7 @@ namespace {
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
-constexpr int N_BUF = 18;
+constexpr int N_BUF = 19;
 struct Layout {
     size_t off[N_BUF];
     size_t total;
@@ -89,6 +90,18 @@ size_t stream_copy_elems(const mulo_model_cfg& c) {
            packed_weight_elems(1, c.vocab, d);
 }
 
+// the largest partial-sum scratch a projection of this model asks for, at the most tokens that stream (or fit)
+size_t ksum_bytes(const mulo_model_cfg& c) {
+    const size_t M = (size_t)c.max_batch * c.max_block;
+    const int Ms = (int)(M < (size_t)STREAM_MAX_TOKENS_COPY ? M : (size_t)STREAM_MAX_TOKENS_COPY);
+    const int d = c.d_model, f = c.d_ffn, V = c.vocab;
+    size_t n = stream_ksum_floats(Ms, 3 * d, d);
+    const size_t others[4] = {stream_ksum_floats(Ms, d, d), stream_ksum_floats(Ms, 2 * f, d), stream_ksum_floats(Ms, d, f),
+                              stream_ksum_floats(Ms, V, d)};
+    for (size_t o : others) n = o > n ? o : n;
+    return n * sizeof(float);
+}
+
 Layout plan(const mulo_model_cfg& c) {
     const size_t M = (size_t)c.max_batch * c.max_block, d = c.d_model, f = c.d_ffn, V = c.vocab;
     const size_t M16 = (M + 15) / 16 * 16;   // the operands of the projections hold whole groups of 16 tokens (fragment order)
@@ -98,7 +111,8 @@ Layout plan(const mulo_model_cfg& c) {
                               M * V * 4, M * V * 4, M * 4, M * 4, M * 4, M * 4, (size_t)c.max_block * 4,
                               c.dtype == MULO_BF16 ? attention_scratch_bytes(c.max_batch, c.n_heads, c.head_dim) : 0,
                               M * 4, M, c.dtype == MULO_BF16 ? M * ((V + 127) / 128) * 8 : 0,
-                              c.dtype == MULO_BF16 && c.stream_copy ? stream_copy_elems(c) * 2 : 0};
+                              c.dtype == MULO_BF16 && c.stream_copy ? stream_copy_elems(c) * 2 : 0,
+                              c.dtype == MULO_BF16 && c.stream_copy ? ksum_bytes(c) : 0};
     Layout l{};
     size_t o = 0;
     for (int i = 0; i < N_BUF; ++i) {
@@ -178,8 +192,11 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     const size_t e = c->esz;
     hipStream_t st = c->st;
     // a handful of tokens: every bf16 projection streams its weights and takes its token operand in fragment order
-    const bool frag = dt == MULO_BF16 && streams_weights(M);
-    const bool wfrag = frag && c->pk_wq != nullptr;
+    // with the weight copy up to 256 tokens stream (above 64 in the kernel that shares the token operand through LDS)
+    const bool has_copy = c->pk_wq != nullptr;
+    const bool frag = dt == MULO_BF16 && M <= (has_copy ? STREAM_MAX_TOKENS_COPY : STREAM_MAX_TOKENS);
+    const bool wfrag = frag && has_copy;
+    const StreamMode sm{frag, wfrag, wfrag ? c->ksums : nullptr};
     { PROF(MULO_PROF_NORM_EMBED); launch_embed(c->w.embed, dt, tok, emb, c->x, M, d, V, st); }
     for (int l = 0; l < m.n_layers; ++l) {
         RopeArgs ra{c->w.rope_cos, c->w.rope_sin, L, P, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l};
@@ -196,16 +213,16 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
         const char* g_ffn = (const char*)c->w.ffn_norm + (size_t)l * d * e;
         { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_attn, dt, c->xh, M, d, m.rms_eps, frag, st); }
         if (dt == MULO_BF16) {
-            { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, wfrag, st); }
+            { PROF(MULO_PROF_GEMM_QKV); launch_gemm_qkv_bf16(c->xh, wq, wk, wv, c->qbuf, kv->k, kv->v, M, d, ra, sm, st); }
             { PROF(MULO_PROF_ATTENTION);
               if (sc) launch_attention_scattered_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, sc->pos_tab, L, sc->hide,
-                                                      sc->P0, sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, st);
+                                                      sc->P0, sc->Lblk, m.n_heads, m.head_dim, m.max_seq, m.max_batch, l, frag, st);
               else launch_attention_bf16(c->qbuf, kv->k, kv->v, c->att, c->attn_part, B, L, P, m.n_heads, m.head_dim,
-                                         m.max_seq, m.max_batch, l, st); }
-            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, wfrag, st); }
+                                         m.max_seq, m.max_batch, l, frag, st); }
+            { PROF(MULO_PROF_GEMM_OUT); launch_gemm_resid_bf16(c->att, wo, c->x, M, d, d, sm, st); }
             { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, g_ffn, dt, c->xh, M, d, m.rms_eps, frag, st); }
-            { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, wfrag, st); }
-            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, wfrag, st); }
+            { PROF(MULO_PROF_GEMM_GATE_UP); launch_gemm_swiglu_bf16(c->xh, wg, wu, c->hmid, M, f, d, sm, st); }
+            { PROF(MULO_PROF_GEMM_DOWN); launch_gemm_resid_bf16(c->hmid, wd, c->x, M, d, f, sm, st); }
         } else {
             const float* xh = (const float*)c->xh;
             { PROF(MULO_PROF_GEMM_QKV);
@@ -228,7 +245,7 @@ bool enqueue_forward(mulo_ctx* c, mulo_kv* kv, int B, int L, int P, const int32_
     }
     { PROF(MULO_PROF_NORM_EMBED); launch_rmsnorm(c->x, c->w.final_norm, dt, c->xh, M, d, m.rms_eps, frag, st); }
     PROF(MULO_PROF_GEMM_LM_HEAD);
-    if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, wfrag ? (const void*)c->pk_lm : c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, wfrag, st);
+    if (dt == MULO_BF16) return launch_gemm_logits_bf16(c->xh, wfrag ? (const void*)c->pk_lm : c->w.lm_head, logits, want_parts ? c->row_parts : nullptr, M, V, d, sm, st);
     launch_gemm_f32((const float*)c->xh, (const float*)c->w.lm_head, logits, M, V, d, V, 0, st);
     return false;
 }
@@ -384,6 +401,7 @@ mulo_status mulo_create(const mulo_model_cfg* cfg, const mulo_weights* w, void* 
     c->isl_hide = (uint8_t*)(b + l.off[15]);
     c->row_parts = c->esz == 2 ? (float*)(b + l.off[16]) : nullptr;
     c->pk_wq = c->pk_wk = c->pk_wv = c->pk_wo = c->pk_gate = c->pk_up = c->pk_down = c->pk_lm = nullptr;
+    c->ksums = cfg->stream_copy ? (float*)(b + l.off[18]) : nullptr;
     if (cfg->stream_copy) {   // bf16 (checked): the second copy of the weights, made once on the context's stream
         const int nl = cfg->n_layers, d = cfg->d_model, f = cfg->d_ffn;
         char* p = b + l.off[17];

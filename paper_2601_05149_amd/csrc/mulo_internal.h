@@ -23,6 +23,29 @@ bool ensure_dynamic_lds(const void* kern, int bytes, int* state);
 // and no lane exchange is needed.  Buffers are sized for whole groups of 16 tokens.
 constexpr int STREAM_MAX_TOKENS = 64;
 inline bool streams_weights(int M) { return M <= STREAM_MAX_TOKENS; }
+// With the context's weight copy in fragment order, launches of up to STREAM_MAX_TOKENS_COPY tokens stream: above
+// STREAM_SHARED_MIN_TOKENS they run in the kernel that shares the token operand through LDS and splits K over workgroups.
+constexpr int STREAM_MAX_TOKENS_COPY = 256;
+#ifndef STREAM_SHARED_MIN_TOKENS
+#define STREAM_SHARED_MIN_TOKENS 64
+#endif
+// How a launch of few tokens runs its projections (decided once per forward, the same for every kernel of it):
+//   stream  the token operands are in fragment order and the projections run in the weight-streaming kernels
+//   w_frag  the weight pointers are the context's copies in fragment order
+//   ksums   scratch for the sums of the K slices (stream_ksum_floats) when w_frag, else nullptr
+struct StreamMode { bool stream, w_frag; float* ksums; };
+// K slices per 128-column group in the LDS-sharing kernel: as many as keep the launch within one round of 256
+// workgroups, at most 8, at least 8 k-steps each.  A function of the projection's shape only, so the order of every
+// sum is fixed by the model.
+inline int stream_ksplit(int ncols, int K) {
+    const int groups = (ncols + 127) / 128, steps = K / 32;
+    int ks = 256 / groups;
+    ks = ks < 1 ? 1 : (ks > 8 ? 8 : ks);
+    const int most = steps / 8 > 1 ? steps / 8 : 1;
+    return ks > most ? most : ks;
+}
+// floats of partial sums such a launch of M tokens over `ncols` output columns (gate|up: 2 f, q|k|v: 3 d) needs
+inline size_t stream_ksum_floats(int M, int ncols, int K) { return (size_t)stream_ksplit(ncols, K) * M * ncols; }
 __host__ __device__ inline int64_t frag_index(int m, int k, int K) {   // in elements; runs of 8 k stay contiguous
     return ((int64_t)(m >> 4) * (K >> 5) + (k >> 5)) * 512 + (((k & 31) >> 3) * 16 + (m & 15)) * 8 + (k & 7);
 }
@@ -105,14 +128,13 @@ void launch_rmsnorm(const float* x, const void* gain, int dtype, void* out, int 
                     hipStream_t st);
 
 // bf16 MFMA GEMMs, C = A[M,K] * W[N,K]^T with fused epilogues
-// w_frag: the weight pointers are the context's copies in fragment order (stream_copy; only launches that stream)
 void launch_gemm_qkv_bf16(const void* xh, const void* wq, const void* wk, const void* wv, void* q_out,
-                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, bool w_frag,
+                          void* k_cache, void* v_cache, int M, int d, const RopeArgs& ra, const StreamMode& sm,
                           hipStream_t st);
-void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, bool w_frag,
+void launch_gemm_resid_bf16(const void* a, const void* w, float* x, int M, int N, int K, const StreamMode& sm,
                             hipStream_t st);
 void launch_gemm_swiglu_bf16(const void* xh, const void* wg, const void* wu, void* h, int M, int f,
-                             int d, bool w_frag, hipStream_t st);
+                             int d, const StreamMode& sm, hipStream_t st);
 // Copies `layers` bf16 matrices [rows, K] (contiguous, rows % 16 == 0 or layers == 1) into fragment order: rows in
 // groups of 16, k in steps of 32, the KB of (group, step) contiguous with lane 16 c + r holding k 8 c .. 8 c + 7 of
 // row r; rows past the last are zeros.  dst holds layers * ceil16(rows) * K elements.
@@ -122,18 +144,19 @@ inline size_t packed_weight_elems(int layers, int rows, int K) { return (size_t)
 // every row (row_parts.h); returns whether they were written (only the kernels whose wavefront tile is 128 columns
 // wide produce them)
 bool launch_gemm_logits_bf16(const void* xh, const void* w, float* logits, float* parts, int M, int V, int d,
-                             bool w_frag, hipStream_t st);
+                             const StreamMode& sm, hipStream_t st);
 size_t attention_scratch_bytes(int max_batch, int n_heads, int head_dim);   // partial results of the key split
+// frag_out: `out` feeds a weight-streaming projection: written in fragment order
 void launch_attention_bf16(const void* q, const void* k_cache, const void* v_cache, void* out, float* scratch,
                            int B, int L, int P, int n_heads, int head_dim, int max_seq, int max_batch,
-                           int layer, hipStream_t st);
+                           int layer, bool frag_out, hipStream_t st);
 // cap single-token queries per sequence at scattered cache rows: slot j of sequence b sits at row
 // pos_tab[b * cap + j] (< 0: unused slot, its output row is zeroed) and attends to rows <= its own except the rows
 // P0 + t of its sequence with hide[b, t] set (t < Lblk; its own row is never hidden).  Rows are in [P0, P0 + Lblk).
 void launch_attention_scattered_bf16(const void* q, const void* k_cache, const void* v_cache, void* out,
                                      float* scratch, int B, const int32_t* pos_tab, int cap, const uint8_t* hide,
                                      int P0, int Lblk, int n_heads, int head_dim, int max_seq, int max_batch,
-                                     int layer, hipStream_t st);
+                                     int layer, bool frag_out, hipStream_t st);
 
 // float32 path (small configurations): plain tiled GEMM + separate elementwise kernels
 void launch_gemm_f32(const float* a, const float* w, float* c, int M, int N, int K, int ldc,

@@ -267,16 +267,18 @@ def frag_to_rows(buf, M, K):
     return buf.reshape(-1)[idx]
 
 
-@pytest.mark.parametrize("B,L,copy", [(3, 1, False), (4, 13, False), (2, 32, False), (3, 1, True), (4, 13, True)])
+@pytest.mark.parametrize("B,L,copy", [(3, 1, False), (4, 13, False), (2, 32, False), (3, 1, True), (4, 13, True),
+                                      (4, 40, True), (2, 100, True)])
 def test_forward_few_tokens_keeps_its_operands_in_fragment_order(B, L, copy):
     """Launches of at most 64 tokens (one, four and four token groups of 16; 3, 52 and 64 tokens) run every projection
     in the weight-streaming kernel, whose token operand the producing kernels leave in the matrix instruction's own
-    order.  One layer: the attention output and silu(gate) * up read back through mulo_workspace_read, put back in
+    order; with the context's weight copy in fragment order so do launches of up to 256 tokens (160 and 200 here: the
+    kernel that shares the token operand through LDS and deals K to several workgroups).  One layer: the attention output and silu(gate) * up read back through mulo_workspace_read, put back in
     row order by the documented formula, are the oracle's stage tensors; the logits are held to the usual bound."""
     m = dict(n_layers=1, d_model=256, n_heads=2, head_dim=128, d_ffn=512, vocab=1024, dtype="bf16", rms_eps=1e-5)
-    Pn, S, M = 70, 112, B * L
+    Pn, S, M = 70, 184, B * L
     w = G.make_weights(m, seed=11)
-    ctx, cos, sin = make_ctx(m, w, B, S, 72, stream_copy=copy)
+    ctx, cos, sin = make_ctx(m, w, B, S, 104, stream_copy=copy)
     kv = mulo.alloc_kv(ctx, DEV)
     dr, du = pair(m, w, cos, sin, B, S)
     pre = G.uniform_tokens((B, Pn), m["vocab"], 11, tag=0)
